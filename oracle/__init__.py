@@ -1,0 +1,18 @@
+"""CPU oracle for the EARS verification step.  TEST INFRASTRUCTURE ONLY.
+
+Only the test-suite, the smoke check and the benchmark's CPU-baseline leg may import this package;
+the GPU library never does, and the two share no code.
+"""
+from .ears_oracle import (  # noqa: F401
+    NDIAG,
+    NSAMP,
+    OracleResult,
+    accept_uniform,
+    build,
+    gumbel,
+    gumbel_uniform,
+    philox4x32_10,
+    softmax,
+    verify,
+    verify_ragged,
+)

@@ -1,0 +1,270 @@
+/*
+ * CPU oracle for the EARS verification step.  TEST INFRASTRUCTURE ONLY (see ears_oracle.h).
+ * Plain sequential fp64; no blocking, fusion or reordering beyond what the paper states.
+ */
+#include "ears_oracle.h"
+
+#include <math.h>
+#include <stdlib.h>
+#include <string.h>
+
+/* ------------------------------------------------------------------------------------------
+ * Philox4x32-10 (Salmon et al., SC'11, Section 3.3 and Table 2 of that paper): each round
+ * multiplies counter words 0 and 2 by two fixed odd constants, keeps the low halves, and mixes
+ * the high halves with the other two words and the round key; the key is bumped by two Weyl
+ * constants between rounds.
+ * ------------------------------------------------------------------------------------------ */
+void ears_oracle_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4]) {
+  uint32_t c0 = ctr[0], c1 = ctr[1], c2 = ctr[2], c3 = ctr[3];
+  uint32_t k0 = key[0], k1 = key[1];
+  for (int round = 0; round < 10; ++round) {
+    uint64_t prod0 = (uint64_t)0xD2511F53u * (uint64_t)c0;
+    uint64_t prod1 = (uint64_t)0xCD9E8D57u * (uint64_t)c2;
+    uint32_t hi0 = (uint32_t)(prod0 >> 32), lo0 = (uint32_t)prod0;
+    uint32_t hi1 = (uint32_t)(prod1 >> 32), lo1 = (uint32_t)prod1;
+    uint32_t n0 = hi1 ^ c1 ^ k0;
+    uint32_t n1 = lo1;
+    uint32_t n2 = hi0 ^ c3 ^ k1;
+    uint32_t n3 = lo0;
+    c0 = n0; c1 = n1; c2 = n2; c3 = n3;
+    k0 += 0x9E3779B9u;
+    k1 += 0xBB67AE85u;
+  }
+  out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+uint32_t ears_oracle_philox_word(uint64_t seed, uint64_t seq, uint32_t pos, uint32_t domain,
+                                 uint32_t blk, uint32_t word) {
+  uint32_t key[2] = {(uint32_t)(seed & 0xffffffffu), (uint32_t)(seed >> 32)};
+  uint32_t ctr[4] = {blk, pos, (uint32_t)(seq & 0xffffffffu),
+                     (domain << 24) | (uint32_t)((seq >> 32) & 0xffffffu)};
+  uint32_t out[4];
+  ears_oracle_philox4x32_10(ctr, key, out);
+  return out[word & 3u];
+}
+
+/* "Sample U_i ~ Uniform(0,1)" (Section 3.2, step 3): the top 24 bits of one Philox word. */
+double ears_oracle_accept_uniform(uint64_t seed, uint64_t seq, uint32_t pos) {
+  uint32_t w = ears_oracle_philox_word(seed, seq, pos, 0u, 0u, 0u);
+  return (double)(w >> 8) * 0x1p-24;
+}
+
+double ears_oracle_gumbel_uniform(uint64_t seed, uint64_t seq, uint32_t pos, uint32_t v) {
+  uint32_t w = ears_oracle_philox_word(seed, seq, pos, 1u, v >> 2, v & 3u);
+  return (double)(w >> 9) * 0x1p-23 + 0x1p-24;
+}
+
+double ears_oracle_gumbel(uint64_t seed, uint64_t seq, uint32_t pos, uint32_t v) {
+  double u = ears_oracle_gumbel_uniform(seed, seq, pos, v);
+  return -log(-log(u));
+}
+
+/* ------------------------------------------------------------------------------------------ */
+
+static double logit_at(const void* row, int dtype, int64_t v) {
+  if (dtype == EARS_ORACLE_BF16) {
+    uint32_t bits = (uint32_t)((const uint16_t*)row)[v] << 16;
+    float f;
+    memcpy(&f, &bits, sizeof f);
+    return (double)f;
+  }
+  return (double)((const float*)row)[v];
+}
+
+static const void* row_ptr(const void* base, int dtype, int64_t row, int V) {
+  size_t esz = (dtype == EARS_ORACLE_BF16) ? 2u : 4u;
+  return (const char*)base + (size_t)row * (size_t)V * esz;
+}
+
+/* "the full distribution over the vocabulary" (Section 3.1), at sampling temperature T
+ * (Section 4.1 uses T = 0.9): p = softmax(l / T), the textbook three passes. */
+double ears_oracle_softmax(const void* row, int dtype, int V, double T, double* p, double* m_out,
+                           double* Z_out) {
+  double m = -INFINITY;
+  for (int v = 0; v < V; ++v) {
+    double l = logit_at(row, dtype, v);
+    if (l > m) m = l;
+  }
+  double Z = 0.0;
+  for (int v = 0; v < V; ++v) {
+    p[v] = exp((logit_at(row, dtype, v) - m) / T);
+    Z += p[v];
+  }
+  double pmax = 0.0;
+  for (int v = 0; v < V; ++v) {
+    p[v] /= Z;
+    if (p[v] > pmax) pmax = p[v];
+  }
+  *m_out = m;
+  *Z_out = Z;
+  return pmax;
+}
+
+/* argmax over v of score(v), lowest index on ties; also the runner-up score. */
+typedef struct {
+  double best, second;
+  int32_t arg;
+} top2_t;
+
+static void top2_init(top2_t* t) {
+  t->best = -INFINITY;
+  t->second = -INFINITY;
+  t->arg = -1;
+}
+
+static void top2_push(top2_t* t, double s, int32_t v) {
+  if (t->arg < 0 || s > t->best) {
+    t->second = (t->arg < 0) ? -INFINITY : t->best;
+    t->best = s;
+    t->arg = v;
+  } else if (s > t->second) {
+    t->second = s;
+  }
+}
+
+int ears_oracle_verify_seq(const void* target_rows, const void* draft_rows, const int32_t* tokens,
+                           int dtype, int K, int V, double T, double beta, uint64_t seed,
+                           uint64_t seq_id, int32_t* accept_len, int32_t* out_tokens, double* diag,
+                           int32_t* path, double* samp) {
+  int rc = 0;
+  double* pt = (double*)malloc((size_t)V * sizeof(double));
+  double* pd = (double*)malloc((size_t)V * sizeof(double));
+  int n = K; /* number of accepted draft tokens: index of the first rejection (Section 3.1) */
+  int first_reject_seen = 0;
+
+  for (int i = 0; i < K; ++i) {
+    /* step 1: P_t(x_i), P_d(x_i), max(P_t) */
+    double mt, Zt, md, Zd;
+    double maxpt = ears_oracle_softmax(row_ptr(target_rows, dtype, i, V), dtype, V, T, pt, &mt, &Zt);
+    (void)ears_oracle_softmax(row_ptr(draft_rows, dtype, i, V), dtype, V, T, pd, &md, &Zd);
+    int32_t x = tokens[i];
+    int valid = (x >= 0 && x < V);
+    double Ptx = valid ? pt[x] : 0.0;
+    double Pdx = valid ? pd[x] : 0.0;
+    /* step 2 with the division guard of Section 3.3 item 2 (epsilon = 1e-10) */
+    double Pd_safe = (Pdx > 1e-10) ? Pdx : 1e-10;
+    double R = Ptx / Pd_safe;
+    /* step 3 */
+    double U = ears_oracle_accept_uniform(seed, seq_id, (uint32_t)i);
+    /* step 4: uncertainty 1 - max P_t and tolerance beta * uncertainty (Section 3.2) */
+    double unc = 1.0 - maxpt;
+    double tol = beta * unc;
+    /* threshold clamp of Section 3.3 item 2 */
+    double thr = U - tol;
+    if (thr < 0.0) thr = 0.0;
+    /* step 5: the three-way decision */
+    int decision;
+    if (!valid) {
+      decision = 0;
+      rc = 1;
+    } else if (R >= U) {
+      decision = 1; /* primary path, identical to the traditional rule */
+    } else if (R >= thr) {
+      decision = 2; /* accepted through the tolerance */
+    } else {
+      decision = 0;
+    }
+    if (decision == 0 && !first_reject_seen) {
+      first_reject_seen = 1;
+      n = i; /* x_i and every later draft token are rejected */
+    }
+    if (diag) {
+      double* d = diag + (size_t)i * EARS_ORACLE_NDIAG;
+      d[0] = mt; d[1] = Zt; d[2] = Ptx; d[3] = md; d[4] = Zd; d[5] = Pdx;
+      d[6] = unc; d[7] = R; d[8] = U; d[9] = thr;
+    }
+    if (path) path[i] = decision;
+  }
+
+  top2_t top;
+  top2_init(&top);
+  double mode;
+  if (n < K) {
+    /* replacement token at the rejected slot: residual distribution norm(max(0, p_t - p_d)),
+     * sampled by Gumbel-max: argmax_v log q(v) + g(v) */
+    double mt, Zt, md, Zd;
+    (void)ears_oracle_softmax(row_ptr(target_rows, dtype, n, V), dtype, V, T, pt, &mt, &Zt);
+    (void)ears_oracle_softmax(row_ptr(draft_rows, dtype, n, V), dtype, V, T, pd, &md, &Zd);
+    mode = 0.0;
+    int any = 0;
+    for (int v = 0; v < V; ++v) {
+      double q = pt[v] - pd[v];
+      if (q > 0.0) {
+        any = 1;
+        top2_push(&top, log(q) + ears_oracle_gumbel(seed, seq_id, (uint32_t)n, (uint32_t)v), v);
+      }
+    }
+    if (!any) {
+      /* empty residual (p_t <= p_d everywhere): fall back to the target distribution itself */
+      mode = 2.0;
+      for (int v = 0; v < V; ++v) {
+        if (pt[v] > 0.0)
+          top2_push(&top, log(pt[v]) + ears_oracle_gumbel(seed, seq_id, (uint32_t)n, (uint32_t)v),
+                    v);
+      }
+    }
+  } else {
+    /* every draft token accepted: bonus token from the target row after the last draft
+     * position; Gumbel-max on the unnormalised log-probabilities l / T */
+    mode = 1.0;
+    const void* row = row_ptr(target_rows, dtype, K, V);
+    for (int v = 0; v < V; ++v) {
+      double l = logit_at(row, dtype, v);
+      if (l > -INFINITY)
+        top2_push(&top, l / T + ears_oracle_gumbel(seed, seq_id, (uint32_t)K, (uint32_t)v), v);
+    }
+  }
+
+  *accept_len = n;
+  for (int i = 0; i <= K; ++i) out_tokens[i] = -1;
+  for (int i = 0; i < n; ++i) out_tokens[i] = tokens[i];
+  out_tokens[n] = top.arg;
+  if (samp) {
+    samp[0] = top.best;
+    samp[1] = top.second;
+    samp[2] = top.best - top.second;
+    samp[3] = mode;
+  }
+  free(pt);
+  free(pd);
+  return rc;
+}
+
+int ears_oracle_verify(const void* target, const void* draft, const int32_t* tokens, int dtype,
+                       int B, int K, int V, double T, double beta, uint64_t seed,
+                       const int64_t* seq_ids, int32_t* accept_len, int32_t* out_tokens,
+                       double* diag, int32_t* path, double* samp, int nthreads) {
+  int rc = 0;
+  if (nthreads < 1) nthreads = 1;
+#pragma omp parallel for num_threads(nthreads) schedule(dynamic, 1) reduction(| : rc)
+  for (int b = 0; b < B; ++b) {
+    uint64_t seq = seq_ids ? (uint64_t)seq_ids[b] : (uint64_t)b;
+    rc |= ears_oracle_verify_seq(
+        row_ptr(target, dtype, (int64_t)b * (K + 1), V), row_ptr(draft, dtype, (int64_t)b * K, V),
+        tokens + (size_t)b * K, dtype, K, V, T, beta, seed, seq, accept_len + b,
+        out_tokens + (size_t)b * (K + 1), diag ? diag + (size_t)b * K * EARS_ORACLE_NDIAG : NULL,
+        path ? path + (size_t)b * K : NULL, samp ? samp + (size_t)b * EARS_ORACLE_NSAMP : NULL);
+  }
+  return rc;
+}
+
+int ears_oracle_verify_ragged(const void* target, const void* draft, const int32_t* tokens,
+                              const int64_t* row_offsets, int dtype, int B, int V, const float* T,
+                              const float* beta, uint64_t seed, const int64_t* seq_ids,
+                              int32_t* accept_len, int32_t* out_tokens, double* diag,
+                              int32_t* path, double* samp, int nthreads) {
+  int rc = 0;
+  if (nthreads < 1) nthreads = 1;
+#pragma omp parallel for num_threads(nthreads) schedule(dynamic, 1) reduction(| : rc)
+  for (int b = 0; b < B; ++b) {
+    int64_t r0 = row_offsets[b];
+    int Kb = (int)(row_offsets[b + 1] - r0);
+    uint64_t seq = seq_ids ? (uint64_t)seq_ids[b] : (uint64_t)b;
+    rc |= ears_oracle_verify_seq(
+        row_ptr(target, dtype, r0 + b, V), row_ptr(draft, dtype, r0, V), tokens + r0, dtype, Kb, V,
+        (double)T[b], (double)beta[b], seed, seq, accept_len + b, out_tokens + r0 + b,
+        diag ? diag + (size_t)r0 * EARS_ORACLE_NDIAG : NULL, path ? path + r0 : NULL,
+        samp ? samp + (size_t)b * EARS_ORACLE_NSAMP : NULL);
+  }
+  return rc;
+}

@@ -1,0 +1,194 @@
+"""ctypes binding of the plain-C CPU oracle (oracle/ears_oracle.c).  TEST INFRASTRUCTURE ONLY.
+
+Inputs are numpy arrays: fp32 logits as float32, bf16 logits as uint16 (the raw bit pattern).
+Nothing here touches the GPU library.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from dataclasses import dataclass
+from typing import Optional
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "ears_oracle.c")
+_LIB = os.path.join(_HERE, "libears_oracle.so")
+
+NDIAG = 10
+NSAMP = 4
+DIAG_NAMES = ("m_t", "Z_t", "P_t_x", "m_d", "Z_d", "P_d_x", "unc", "R", "U", "thr")
+
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (a second or so).  Returns the path of the shared library."""
+    stale = (not os.path.exists(_LIB)) or os.path.getmtime(_LIB) < max(
+        os.path.getmtime(_SRC), os.path.getmtime(os.path.join(_HERE, "ears_oracle.h")))
+    if force or stale:
+        tmp = _LIB + ".tmp.%d" % os.getpid()
+        subprocess.check_call(
+            ["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-fopenmp", "-ffp-contract=off",
+             "-Wall", "-Wextra", "-o", tmp, _SRC, "-lm"])
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is not None:
+        return _lib
+    build()
+    lib = ctypes.CDLL(_LIB)
+    c = ctypes
+    u32p = c.POINTER(c.c_uint32)
+    lib.ears_oracle_philox4x32_10.argtypes = [u32p, u32p, u32p]
+    lib.ears_oracle_philox4x32_10.restype = None
+    lib.ears_oracle_philox_word.argtypes = [c.c_uint64, c.c_uint64, c.c_uint32, c.c_uint32,
+                                            c.c_uint32, c.c_uint32]
+    lib.ears_oracle_philox_word.restype = c.c_uint32
+    for name in ("ears_oracle_accept_uniform",):
+        f = getattr(lib, name)
+        f.argtypes = [c.c_uint64, c.c_uint64, c.c_uint32]
+        f.restype = c.c_double
+    for name in ("ears_oracle_gumbel_uniform", "ears_oracle_gumbel"):
+        f = getattr(lib, name)
+        f.argtypes = [c.c_uint64, c.c_uint64, c.c_uint32, c.c_uint32]
+        f.restype = c.c_double
+    lib.ears_oracle_softmax.argtypes = [c.c_void_p, c.c_int, c.c_int, c.c_double, c.c_void_p,
+                                        c.POINTER(c.c_double), c.POINTER(c.c_double)]
+    lib.ears_oracle_softmax.restype = c.c_double
+    lib.ears_oracle_verify.argtypes = [
+        c.c_void_p, c.c_void_p, c.c_void_p, c.c_int, c.c_int, c.c_int, c.c_int, c.c_double,
+        c.c_double, c.c_uint64, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p,
+        c.c_void_p, c.c_int]
+    lib.ears_oracle_verify.restype = c.c_int
+    lib.ears_oracle_verify_ragged.argtypes = [
+        c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_int, c.c_int, c.c_int, c.c_void_p,
+        c.c_void_p, c.c_uint64, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p,
+        c.c_void_p, c.c_int]
+    lib.ears_oracle_verify_ragged.restype = c.c_int
+    _lib = lib
+    return lib
+
+
+def _dtype_code(a: np.ndarray) -> int:
+    if a.dtype == np.float32:
+        return 0
+    if a.dtype == np.uint16:
+        return 1
+    raise TypeError("logits must be float32 or uint16 (bf16 bit pattern), got %s" % a.dtype)
+
+
+def _ptr(a: Optional[np.ndarray]):
+    return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+
+
+def philox4x32_10(ctr, key):
+    lib = _load()
+    c = (ctypes.c_uint32 * 4)(*[int(x) & 0xFFFFFFFF for x in ctr])
+    k = (ctypes.c_uint32 * 2)(*[int(x) & 0xFFFFFFFF for x in key])
+    o = (ctypes.c_uint32 * 4)()
+    lib.ears_oracle_philox4x32_10(c, k, o)
+    return tuple(int(x) for x in o)
+
+
+def philox_word(seed, seq, pos, domain, blk, word) -> int:
+    return int(_load().ears_oracle_philox_word(seed, seq, pos, domain, blk, word))
+
+
+def accept_uniform(seed: int, seq: int, pos: int) -> float:
+    return float(_load().ears_oracle_accept_uniform(seed, seq, pos))
+
+
+def gumbel_uniform(seed: int, seq: int, pos: int, v: int) -> float:
+    return float(_load().ears_oracle_gumbel_uniform(seed, seq, pos, v))
+
+
+def gumbel(seed: int, seq: int, pos: int, v: int) -> float:
+    return float(_load().ears_oracle_gumbel(seed, seq, pos, v))
+
+
+def softmax(row: np.ndarray, T: float):
+    """Returns (p[V] float64, m, Z, max p) of one logit row."""
+    lib = _load()
+    row = np.ascontiguousarray(row)
+    V = row.shape[0]
+    p = np.empty(V, dtype=np.float64)
+    m = ctypes.c_double()
+    Z = ctypes.c_double()
+    pmax = lib.ears_oracle_softmax(_ptr(row), _dtype_code(row), V, float(T), _ptr(p),
+                                   ctypes.byref(m), ctypes.byref(Z))
+    return p, m.value, Z.value, float(pmax)
+
+
+@dataclass
+class OracleResult:
+    accept_len: np.ndarray  # [B] int32
+    tokens: np.ndarray      # [B, K+1] int32 (ragged: packed like target rows)
+    diag: np.ndarray        # [B, K, NDIAG] float64 (ragged: [rows, NDIAG])
+    path: np.ndarray        # [B, K] int32 (ragged: [rows])
+    samp: np.ndarray        # [B, NSAMP] float64
+    status: int             # 1 if some draft token was out of range
+
+    def d(self, name: str) -> np.ndarray:
+        return self.diag[..., DIAG_NAMES.index(name)]
+
+
+def verify(target: np.ndarray, draft: np.ndarray, tokens: np.ndarray, T: float, beta: float,
+           seed: int, seq_ids: Optional[np.ndarray] = None, nthreads: int = 1) -> OracleResult:
+    """target [B, K+1, V], draft [B, K, V] (float32 or uint16 bf16 bits), tokens [B, K] int32."""
+    lib = _load()
+    target = np.ascontiguousarray(target)
+    draft = np.ascontiguousarray(draft)
+    tokens = np.ascontiguousarray(tokens, dtype=np.int32)
+    B, K1, V = target.shape
+    K = K1 - 1
+    assert draft.shape == (B, K, V) and tokens.shape == (B, K)
+    assert _dtype_code(target) == _dtype_code(draft)
+    if seq_ids is not None:
+        seq_ids = np.ascontiguousarray(seq_ids, dtype=np.int64)
+        assert seq_ids.shape == (B,)
+    acc = np.empty(B, dtype=np.int32)
+    out = np.empty((B, K + 1), dtype=np.int32)
+    diag = np.empty((B, K, NDIAG), dtype=np.float64)
+    path = np.empty((B, K), dtype=np.int32)
+    samp = np.empty((B, NSAMP), dtype=np.float64)
+    rc = lib.ears_oracle_verify(_ptr(target), _ptr(draft), _ptr(tokens), _dtype_code(target), B, K,
+                                V, float(T), float(beta), int(seed), _ptr(seq_ids), _ptr(acc),
+                                _ptr(out), _ptr(diag), _ptr(path), _ptr(samp), int(nthreads))
+    return OracleResult(acc, out, diag, path, samp, int(rc))
+
+
+def verify_ragged(target: np.ndarray, draft: np.ndarray, tokens: np.ndarray,
+                  row_offsets: np.ndarray, T: np.ndarray, beta: np.ndarray, seed: int,
+                  seq_ids: Optional[np.ndarray] = None, nthreads: int = 1) -> OracleResult:
+    """target [R + B, V], draft [R, V], tokens [R]; row_offsets [B+1] int64 over draft rows."""
+    lib = _load()
+    target = np.ascontiguousarray(target)
+    draft = np.ascontiguousarray(draft)
+    tokens = np.ascontiguousarray(tokens, dtype=np.int32)
+    row_offsets = np.ascontiguousarray(row_offsets, dtype=np.int64)
+    T = np.ascontiguousarray(T, dtype=np.float32)
+    beta = np.ascontiguousarray(beta, dtype=np.float32)
+    B = row_offsets.shape[0] - 1
+    R = int(row_offsets[-1])
+    V = target.shape[1]
+    assert row_offsets[0] == 0 and np.all(np.diff(row_offsets) >= 1)
+    assert target.shape == (R + B, V) and draft.shape == (R, V) and tokens.shape == (R,)
+    assert T.shape == (B,) and beta.shape == (B,)
+    if seq_ids is not None:
+        seq_ids = np.ascontiguousarray(seq_ids, dtype=np.int64)
+    acc = np.empty(B, dtype=np.int32)
+    out = np.empty(R + B, dtype=np.int32)
+    diag = np.empty((R, NDIAG), dtype=np.float64)
+    path = np.empty(R, dtype=np.int32)
+    samp = np.empty((B, NSAMP), dtype=np.float64)
+    rc = lib.ears_oracle_verify_ragged(_ptr(target), _ptr(draft), _ptr(tokens), _ptr(row_offsets),
+                                       _dtype_code(target), B, V, _ptr(T), _ptr(beta), int(seed),
+                                       _ptr(seq_ids), _ptr(acc), _ptr(out), _ptr(diag), _ptr(path),
+                                       _ptr(samp), int(nthreads))
+    return OracleResult(acc, out, diag, path, samp, int(rc))
