@@ -1,0 +1,202 @@
+#!/usr/bin/env python3
+"""Benchmark of the EARS verification step on one MI355X.
+
+A step is one whole `ears_verify_bf16` call (row statistics, decision scan, replacement / bonus
+sampling) over one synthetic batch already resident in HBM.  Prints ONE JSON line on stdout.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W]
+"""
+from __future__ import annotations
+
+import argparse
+import hashlib
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E peak
+WORKLOAD_INDEX = 2              # B=256, K=8, V=128256, bf16: the configuration the metric is quoted on
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "traffic_row_stats_c2.json")
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def kernel_source_hash() -> str:
+    h = hashlib.sha256()
+    for rel in ("paper_2512_13194_amd/csrc/ears_kernels.hip", "paper_2512_13194_amd/csrc/ears_device.h"):
+        with open(os.path.join(ROOT, rel), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()[:16]
+
+
+def measured_traffic():
+    """HBM bytes per row-statistics launch from the committed rocprofv3 counter runs, or None when
+    there are none or the kernel source has changed since they were taken."""
+    try:
+        with open(TRAFFIC_FILE) as f:
+            t = json.load(f)
+    except OSError:
+        return None
+    if t.get("kernel_source_hash") != kernel_source_hash():
+        return None
+    return t.get("hbm_bytes_per_launch")
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=40)
+    ap.add_argument("--warmup", type=int, default=8)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        log("bench.py: this build runs on ONE GPU; sequences are independent, so more GPUs would "
+            "each take a share of the batch with no exchange. Re-run with --gpus 1.")
+        return 2
+
+    import torch
+    import paper_2512_13194_amd as ears
+    from paper_2512_13194_amd import inputs
+
+    ears.lib()                    # raises when libears.so is missing: there is no fallback path
+    if not torch.cuda.is_available():
+        log("bench.py: no GPU visible")
+        return 3
+    torch.cuda.set_device(0)
+    cfg = inputs.CONFIGS[WORKLOAD_INDEX]
+    B, K, V = cfg["B"], cfg["K"], cfg["V"]
+    T = cfg["temperatures"][0]
+    betas = cfg["betas"]
+    seed0 = cfg["seed"]
+    esz = 2
+    log("generating workload %s on the GPU ..." % cfg["name"])
+    batch = inputs.make_config(WORKLOAD_INDEX, device="cuda")
+    acc = torch.empty(B, dtype=torch.int32, device="cuda")
+    tok = torch.empty(B, K + 1, dtype=torch.int32, device="cuda")
+    torch.cuda.synchronize()
+
+    def step(i):
+        # beta cycles through the workload's sweep; the seed changes every step as it would
+        # between decoding steps
+        ears.ears_verify_bf16(batch.target, batch.draft, batch.tokens, T, betas[i % len(betas)],
+                              seed0 + i, out_accept_len=acc, out_tokens=tok)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    positions_per_s = B * K / (ms_per_step * 1e-3)
+
+    # algorithmic bytes of a whole call: every target row 0..K-1 and every draft row once, plus
+    # the row pair (rejected) or the single bonus row (all accepted) the sampler re-reads
+    rejected = []
+    for i in range(len(betas)):
+        step(i)
+        torch.cuda.synchronize()
+        rejected.append(int((acc < K).sum().item()))
+    mean_rej = sum(rejected) / len(rejected)
+    k1_bytes = 2 * B * K * V * esz
+    call_bytes = k1_bytes + (2 * mean_rej + (B - mean_rej)) * V * esz
+    call_gbps = call_bytes / (ms_per_step * 1e-3) / 1e9
+
+    # dominant kernel: the row-statistics pass.  Its duration is measured with HIP events on the
+    # stream it is launched on, stage by stage, over the same number of steps.
+    ws = torch.empty(ears.ears_workspace_bytes(B * K, B, V), dtype=torch.uint8, device="cuda")
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+          for _ in range(args.steps)]
+    for i in range(max(2, args.warmup // 2)):
+        ears.ears_verify_ex(batch.target, batch.draft, batch.tokens, temperature=T, beta=betas[0],
+                            seed=seed0, workspace=ws, stages=ears.EARS_STAGE_STATS,
+                            out_accept_len=acc, out_tokens=tok.view(-1))
+    torch.cuda.synchronize()
+    for i in range(args.steps):
+        ev[i][0].record()
+        ears.ears_verify_ex(batch.target, batch.draft, batch.tokens, temperature=T, beta=betas[0],
+                            seed=seed0 + i, workspace=ws, stages=ears.EARS_STAGE_STATS,
+                            out_accept_len=acc, out_tokens=tok.view(-1))
+        ev[i][1].record()
+        ears.ears_verify_ex(batch.target, batch.draft, batch.tokens, temperature=T,
+                            beta=betas[i % len(betas)], seed=seed0 + i, workspace=ws,
+                            stages=ears.EARS_STAGE_DECIDE | ears.EARS_STAGE_SAMPLE,
+                            out_accept_len=acc, out_tokens=tok.view(-1))
+    torch.cuda.synchronize()
+    k1_ms = sum(a.elapsed_time(b) for a, b in ev) / args.steps
+    k1_gbps = k1_bytes / (k1_ms * 1e-3) / 1e9
+
+    # practical ceiling: a read-only streaming kernel over the same two buffers
+    sink = None
+    for _ in range(3):
+        sink = ears.ears_bench_read(batch.target, sink)
+        ears.ears_bench_read(batch.draft, sink)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    reps = 10
+    for _ in range(reps):
+        ears.ears_bench_read(batch.target, sink)
+        ears.ears_bench_read(batch.draft, sink)
+    e1.record()
+    torch.cuda.synchronize()
+    read_bytes = (batch.target.numel() + batch.draft.numel()) * esz
+    read_gbps = read_bytes * reps / (e0.elapsed_time(e1) * 1e-3) / 1e9
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+        try:
+            ncores = len(os.sched_getaffinity(0))
+        except AttributeError:
+            ncores = os.cpu_count() or 1
+        threads = max(1, min(16, ncores))
+        tgt = inputs.logits_to_numpy(batch.target)
+        drf = inputs.logits_to_numpy(batch.draft)
+        tk = batch.tokens.cpu().numpy()
+        c0 = time.perf_counter()
+        oracle.verify(tgt, drf, tk, T, betas[1], seed0, nthreads=threads)
+        c1 = time.perf_counter()
+        cpu = {"value": B * K / (c1 - c0), "unit": "positions/s", "cores": threads, "kind": "oracle",
+               "sample": "the whole %s batch once (%d sequences, beta=%s), fp64 three-pass oracle, "
+                         "one OpenMP thread per sequence, %.1f s wall" % (cfg["name"], B, betas[1], c1 - c0)}
+
+    out = {
+        "metric": "verified_draft_positions_per_sec",
+        "value": positions_per_s,
+        "unit": "positions/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": cfg["name"], "B": B, "K": K, "V": V, "temperature": T,
+                   "betas_cycled": betas, "entry_point": "ears_verify_bf16",
+                   "mean_rejected_sequences": mean_rej},
+        "whole_call": {"algorithmic_bytes": call_bytes, "achieved_GBps": call_gbps,
+                       "frac_of_hbm_peak": call_gbps / HBM_PEAK_GBPS},
+        "roofline": {"bound": "hbm", "kernel": "row_stats_kernel<BF16>", "achieved": k1_gbps,
+                     "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": k1_gbps / HBM_PEAK_GBPS,
+                     "traffic": measured_traffic(), "algorithmic_bytes_per_launch": k1_bytes,
+                     "avg_launch_ms": k1_ms,
+                     "stream_read_ceiling_GBps": read_gbps},
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(out), flush=True)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

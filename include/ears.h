@@ -1,0 +1,183 @@
+/*
+ * ears.h - C ABI of the EARS verification step for AMD MI355X (gfx950).
+ *
+ * EARS (Efficient Adaptive Rejection Sampling) verifies the K draft tokens of every sequence of a
+ * speculative-decoding step against the target model's logits.  For sequence b and draft
+ * position i (0-based), with p_t = softmax(target_logits[b,i,:] / T) and
+ * p_d = softmax(draft_logits[b,i,:] / T), x = draft_tokens[b,i]:
+ *
+ *   uncertainty  unc = 1 - max_v p_t(v)                         (paper Section 3.2)
+ *   tolerance    Tol = beta * unc                               (Section 3.2, "Dynamic Tolerance")
+ *   ratio        R   = p_t(x) / max(p_d(x), 1e-10)              (Section 3.2 step 2; guard 3.3.2)
+ *   threshold    thr = max(U - Tol, 0),  U ~ Uniform[0,1)       (Section 3.2 step 3; clamp 3.3.2)
+ *   accept x  iff  R >= thr                                     (Section 3.2 step 5)
+ *
+ * The first rejected position n ends the accepted prefix (Section 3.1).  At slot n the library
+ * emits a replacement token drawn from norm(max(0, p_t - p_d)) of position n (the residual
+ * distribution of the standard speculative-sampling scheme the paper builds on, its references
+ * [1] and [2]); when all K tokens are accepted (n = K) it emits a bonus token drawn from
+ * softmax(target_logits[b,K,:] / T).  Both draws are Gumbel-max with counter-based
+ * Philox4x32-10 noise keyed on (seed, sequence id, position, vocabulary index), so a call is a
+ * pure function of its arguments.  max_v p_t(v) is obtained in the same single pass over the row
+ * that yields p_t(x) (max p = 1/Z with Z the sum of exp((l - max l)/T)); the per-row statistics
+ * are kept in the workspace and re-used by the sampling pass, which is the "pre-computation and
+ * delayed lookup" of Section 3.3 item 1.
+ *
+ * Conventions
+ *  - Every pointer is a DEVICE pointer on the current HIP device unless marked "host".
+ *  - The caller owns every buffer.  Inputs are only read.  Outputs are fully overwritten.
+ *  - Calls enqueue work on `stream` (a hipStream_t passed as void*; NULL = the null stream) and
+ *    return without synchronising; outputs are valid once the caller has synchronised `stream`.
+ *  - Return value: an ears_status.  All argument checks happen on the host before any HIP call.
+ *  - Logits: finite values and -inf (a masked vocabulary entry, probability 0) are supported as
+ *    long as every row has a finite entry; NaN and +inf are undefined behaviour.
+ *  - A draft token outside [0, V) is rejected at its position and sets bit 0 of the optional
+ *    device status word.
+ *  - Two calls that share a workspace (or the library-owned scratch of the simple entry points)
+ *    must not overlap in time.
+ */
+#ifndef EARS_H
+#define EARS_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum ears_status {
+  EARS_OK = 0,
+  EARS_ERR_NULL = 1,      /* a required pointer is NULL */
+  EARS_ERR_SHAPE = 2,     /* B, K, V or total_draft_rows out of range */
+  EARS_ERR_PARAM = 3,     /* temperature not finite or <= 0; beta not finite or < 0; bad stages */
+  EARS_ERR_ALIGN = 4,     /* a pointer is not aligned as documented */
+  EARS_ERR_DTYPE = 5,     /* dtype is neither EARS_F32 nor EARS_BF16 */
+  EARS_ERR_WORKSPACE = 6, /* workspace NULL or smaller than ears_workspace_bytes() */
+  EARS_ERR_HIP = 7        /* a HIP runtime call or kernel launch failed */
+} ears_status;
+
+typedef enum ears_dtype {
+  EARS_F32 = 0, /* IEEE binary32 logits */
+  EARS_BF16 = 1 /* bfloat16 logits (upper half of a binary32) */
+} ears_dtype;
+
+/* Stages of one verification call (Section 3.2 steps, Section 3.3 item 1).  A call may run a
+ * subset: the statistics stage can run right after the target forward pass and the other two
+ * later, against the statistics cached in the same workspace. */
+enum {
+  EARS_STAGE_STATS = 1,  /* step 1: per row max, sum-exp, logit of the draft token */
+  EARS_STAGE_DECIDE = 2, /* steps 2-5 + first-rejection scan: accept lengths, accepted prefix */
+  EARS_STAGE_SAMPLE = 4, /* replacement / bonus token at slot n */
+  EARS_STAGE_ALL = 7
+};
+
+/* Number of doubles per (sequence, position) in `out_stats`:
+ *   0 m_t  1 Z_t  2 p_t(x)  3 m_d  4 Z_d  5 p_d(x)  6 unc  7 R  8 U  9 thr          */
+#define EARS_NSTATS 10
+
+/* Human-readable name of a status code (host pointer to a static string). */
+const char* ears_status_string(int status);
+
+/* ---------------------------------------------------------------------------------------------
+ * Rectangular batch (the problem statement of Section 3.1: gamma = K draft tokens per sequence).
+ *   target_logits  [B, K+1, V] row-major; row K of each sequence is only read for the bonus token
+ *   draft_logits   [B, K,   V] row-major
+ *   draft_tokens   [B, K] int32
+ *   temperature    T > 0 (sampling temperature, Section 4.1); beta >= 0 (base tolerance)
+ *   seed           RNG seed; vary it between decoding steps.  Sequence b uses RNG id b.
+ *   out_accept_len [B] int32 in [0, K]
+ *   out_tokens     [B, K+1] int32: the accepted prefix, then the replacement / bonus token,
+ *                  then -1
+ * Logit base pointers must be 16-byte aligned, int32 buffers 4-byte aligned.  Any V >= 1 works;
+ * rows whose byte length is a multiple of 16 take the vectorised path.
+ * These entry points keep their scratch in a library-owned, lazily grown per-device buffer
+ * (ears_release() frees it); after the first call of a given size they allocate nothing.
+ * ------------------------------------------------------------------------------------------- */
+int ears_verify_f32(const float* target_logits, const float* draft_logits,
+                    const int32_t* draft_tokens, int B, int K, int V, float temperature,
+                    float beta, uint64_t seed, int32_t* out_accept_len, int32_t* out_tokens,
+                    void* stream);
+
+int ears_verify_bf16(const void* target_logits, const void* draft_logits,
+                     const int32_t* draft_tokens, int B, int K, int V, float temperature,
+                     float beta, uint64_t seed, int32_t* out_accept_len, int32_t* out_tokens,
+                     void* stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * Ragged batch: per-sequence draft length K_b >= 1, temperature and beta (the gathered
+ * "active sequences" layout of Section 3.3 item 3).
+ *   row_offsets      [B+1] int64, device; CSR over the packed DRAFT rows: sequence b owns draft
+ *                    rows row_offsets[b] .. row_offsets[b+1); row_offsets[0] = 0
+ *   total_draft_rows host value of row_offsets[B] (the caller sized its buffers with it)
+ *   target_logits    [total_draft_rows + B, V]: the K_b + 1 target rows of sequence b start at
+ *                    packed row row_offsets[b] + b
+ *   draft_logits     [total_draft_rows, V]; draft_tokens [total_draft_rows]
+ *   temperature,beta [B] float32, device, per sequence (each T > 0, beta >= 0; not checked)
+ *   out_accept_len   [B]; out_tokens [total_draft_rows + B], packed like the target rows
+ * ------------------------------------------------------------------------------------------- */
+int ears_verify_ragged_f32(const float* target_logits, const float* draft_logits,
+                           const int32_t* draft_tokens, const int64_t* row_offsets,
+                           int64_t total_draft_rows, int B, int V, const float* temperature,
+                           const float* beta, uint64_t seed, int32_t* out_accept_len,
+                           int32_t* out_tokens, void* stream);
+
+int ears_verify_ragged_bf16(const void* target_logits, const void* draft_logits,
+                            const int32_t* draft_tokens, const int64_t* row_offsets,
+                            int64_t total_draft_rows, int B, int V, const float* temperature,
+                            const float* beta, uint64_t seed, int32_t* out_accept_len,
+                            int32_t* out_tokens, void* stream);
+
+/* Bytes of caller-owned workspace ears_verify_ex needs for a problem with this many packed draft
+ * rows (B*K for a rectangular batch), B sequences and vocabulary V.  Returns 0 on invalid sizes.
+ * The workspace must be 256-byte aligned. */
+size_t ears_workspace_bytes(int64_t total_draft_rows, int B, int V);
+
+/* ---------------------------------------------------------------------------------------------
+ * Full-control entry point; the four above are thin wrappers of it.
+ *   dtype            ears_dtype of both logit buffers
+ *   row_offsets      NULL for a rectangular batch (then K is used and total_draft_rows must be
+ *                    B*K); otherwise the CSR offsets of a ragged batch (then K is ignored)
+ *   temperature_per_seq, beta_per_seq   device [B] or NULL; when NULL the scalar is used
+ *   seq_ids          device [B] int64 or NULL: RNG id of each sequence (low 56 bits used);
+ *                    NULL means 0..B-1.  With explicit ids a sequence's result does not depend
+ *                    on its slot in the batch.
+ *   workspace        device, >= ears_workspace_bytes(total_draft_rows, B, V) bytes, 256-byte
+ *                    aligned; holds the cached row statistics between stages
+ *   stages           OR of EARS_STAGE_*; DECIDE needs STATS to have run on the same inputs and
+ *                    workspace, SAMPLE needs DECIDE (out_accept_len is read back by SAMPLE)
+ *   out_stats        optional device [total_draft_rows, EARS_NSTATS] float64 (written by DECIDE)
+ *   out_path         optional device [total_draft_rows] int32, per position independent of the
+ *                    prefix: 0 reject, 1 accepted by R >= U, 2 accepted only through the
+ *                    tolerance (the three branches of Section 3.2 step 5)
+ *   status_word      optional device uint32; bits are OR-ed in, never cleared:
+ *                    bit 0 = some draft token was outside [0, V)
+ * ------------------------------------------------------------------------------------------- */
+int ears_verify_ex(int dtype, const void* target_logits, const void* draft_logits,
+                   const int32_t* draft_tokens, const int64_t* row_offsets,
+                   int64_t total_draft_rows, int B, int K, int V, float temperature, float beta,
+                   const float* temperature_per_seq, const float* beta_per_seq, uint64_t seed,
+                   const int64_t* seq_ids, void* workspace, size_t workspace_bytes, int stages,
+                   int32_t* out_accept_len, int32_t* out_tokens, double* out_stats,
+                   int32_t* out_path, uint32_t* status_word, void* stream);
+
+/* Frees the library-owned scratch of the simple entry points on every device (synchronises). */
+void ears_release(void);
+
+/* ---------------------------------------------------------------------------------------------
+ * Measurement aids (not part of the method): a read-only streaming kernel and a plain copy, used
+ * to report the practical HBM ceiling next to the verification kernels and to calibrate the
+ * profiler's byte counters against a transfer of known size.
+ *   ears_bench_read: reads `bytes` (multiple of 16, src 16-byte aligned) and writes one 32-bit
+ *                    checksum per workgroup to sink (device, >= 4 * ears_bench_read_sink_words()
+ *                    bytes)
+ *   ears_bench_copy: dst[0..bytes) = src[0..bytes), both 16-byte aligned, bytes multiple of 16
+ * ------------------------------------------------------------------------------------------- */
+int ears_bench_read_sink_words(void);
+int ears_bench_read(const void* src, size_t bytes, uint32_t* sink, void* stream);
+int ears_bench_copy(void* dst, const void* src, size_t bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* EARS_H */

@@ -1,0 +1,221 @@
+// Device-side building blocks of the EARS verification kernels (gfx950, wave64).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace ears {
+
+constexpr int kWave = 64;
+constexpr int kBlock = 256;             // threads per workgroup: 4 waves
+constexpr int kWavesPerBlock = kBlock / kWave;
+
+// Everything a kernel needs to locate its rows.  Rectangular batches have row_offsets == nullptr:
+// sequence b then owns draft rows b*K .. b*K+K-1.  In both layouts draft row r of sequence b
+// pairs with target row r + b (every earlier sequence has one extra, "bonus", target row).
+struct Problem {
+  const void* target;
+  const void* draft;
+  const int32_t* tokens;
+  const int64_t* row_offsets;
+  int64_t R;  // packed draft rows
+  int B;
+  int K;
+  int V;
+  float T;
+  float beta;
+  const float* T_seq;
+  const float* beta_seq;
+  uint64_t seed;
+  const int64_t* seq_ids;
+  // cached row statistics, index 2*r + which (0 target, 1 draft)
+  double* Z;
+  float* m;
+  float* lx;
+  // outputs
+  int32_t* accept_len;
+  int32_t* out_tokens;
+  double* out_stats;
+  int32_t* out_path;
+  uint32_t* status_word;
+};
+
+__device__ __forceinline__ int seq_of_row(const Problem& p, int64_t r) {
+  if (p.row_offsets == nullptr) return (int)(r / p.K);
+  int lo = 0, hi = p.B;  // invariant: off[lo] <= r < off[hi]
+  while (hi - lo > 1) {
+    int mid = (lo + hi) >> 1;
+    if (p.row_offsets[mid] <= r) lo = mid; else hi = mid;
+  }
+  return lo;
+}
+
+__device__ __forceinline__ int64_t seq_row_begin(const Problem& p, int b) {
+  return p.row_offsets ? p.row_offsets[b] : (int64_t)b * p.K;
+}
+__device__ __forceinline__ int seq_len(const Problem& p, int b) {
+  return p.row_offsets ? (int)(p.row_offsets[b + 1] - p.row_offsets[b]) : p.K;
+}
+__device__ __forceinline__ float seq_temperature(const Problem& p, int b) {
+  return p.T_seq ? p.T_seq[b] : p.T;
+}
+__device__ __forceinline__ float seq_beta(const Problem& p, int b) {
+  return p.beta_seq ? p.beta_seq[b] : p.beta;
+}
+__device__ __forceinline__ uint64_t seq_rng_id(const Problem& p, int b) {
+  return p.seq_ids ? (uint64_t)p.seq_ids[b] : (uint64_t)b;
+}
+
+// ---- logits --------------------------------------------------------------------------------
+struct F32 {
+  using storage = float;
+  static constexpr int kPerVec = 4;  // elements in one 16-byte load
+  static __device__ __forceinline__ float load(const void* base, int64_t i) {
+    return static_cast<const float*>(base)[i];
+  }
+  static __device__ __forceinline__ void unpack(const uint4& v, float (&f)[4]) {
+    f[0] = __uint_as_float(v.x); f[1] = __uint_as_float(v.y);
+    f[2] = __uint_as_float(v.z); f[3] = __uint_as_float(v.w);
+  }
+  static __device__ __forceinline__ uint4 neg_inf_vec() {
+    return make_uint4(0xFF800000u, 0xFF800000u, 0xFF800000u, 0xFF800000u);
+  }
+};
+
+struct BF16 {
+  using storage = uint16_t;
+  static constexpr int kPerVec = 8;
+  static __device__ __forceinline__ float load(const void* base, int64_t i) {
+    return __uint_as_float((uint32_t)static_cast<const uint16_t*>(base)[i] << 16);
+  }
+  // a dword holds two bf16: the low half is the element with the lower index
+  static __device__ __forceinline__ void unpack(const uint4& v, float (&f)[8]) {
+    f[0] = __uint_as_float(v.x << 16); f[1] = __uint_as_float(v.x & 0xFFFF0000u);
+    f[2] = __uint_as_float(v.y << 16); f[3] = __uint_as_float(v.y & 0xFFFF0000u);
+    f[4] = __uint_as_float(v.z << 16); f[5] = __uint_as_float(v.z & 0xFFFF0000u);
+    f[6] = __uint_as_float(v.w << 16); f[7] = __uint_as_float(v.w & 0xFFFF0000u);
+  }
+  static __device__ __forceinline__ uint4 neg_inf_vec() {
+    return make_uint4(0xFF80FF80u, 0xFF80FF80u, 0xFF80FF80u, 0xFF80FF80u);
+  }
+};
+
+// ---- Philox4x32-10 (Salmon et al., SC'11) ----------------------------------------------------
+// Ten rounds; each multiplies counter words 0 and 2 by fixed odd constants and mixes the high
+// halves with the other words and the round key, which advances by two Weyl constants.
+struct Philox {
+  uint32_t w[4];
+};
+
+__device__ __forceinline__ Philox philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
+                                                uint32_t k0, uint32_t k1) {
+#pragma unroll
+  for (int i = 0; i < 10; ++i) {
+    const uint64_t a = (uint64_t)0xD2511F53u * c0;
+    const uint64_t b = (uint64_t)0xCD9E8D57u * c2;
+    const uint32_t n0 = (uint32_t)(b >> 32) ^ c1 ^ k0;
+    const uint32_t n2 = (uint32_t)(a >> 32) ^ c3 ^ k1;
+    c1 = (uint32_t)b;
+    c3 = (uint32_t)a;
+    c0 = n0;
+    c2 = n2;
+    k0 += 0x9E3779B9u;
+    k1 += 0xBB67AE85u;
+  }
+  Philox r;
+  r.w[0] = c0; r.w[1] = c1; r.w[2] = c2; r.w[3] = c3;
+  return r;
+}
+
+// counter = (block, position, seq low 32, domain << 24 | seq bits 32..55); key = seed halves.
+// domain 0: acceptance uniform (block 0, word 0); domain 1: Gumbel noise, block = v >> 2,
+// word = v & 3.
+__device__ __forceinline__ Philox noise_block(uint64_t seed, uint64_t seq, uint32_t pos,
+                                              uint32_t domain, uint32_t blk) {
+  return philox4x32_10(blk, pos, (uint32_t)seq, (domain << 24) | ((uint32_t)(seq >> 32) & 0xFFFFFFu),
+                       (uint32_t)seed, (uint32_t)(seed >> 32));
+}
+
+// U in [0,1) on a 2^-24 grid; u in (0,1) on a 2^-23 grid offset by 2^-24.  Both exact in fp32.
+__device__ __forceinline__ double accept_uniform(uint64_t seed, uint64_t seq, uint32_t pos) {
+  return (double)(noise_block(seed, seq, pos, 0u, 0u).w[0] >> 8) * 0x1p-24;
+}
+__device__ __forceinline__ float gumbel_uniform_from_word(uint32_t w) {
+  return (float)(w >> 9) * 0x1p-23f + 0x1p-24f;  // exact: 23-bit integer, then one more bit
+}
+
+// ---- wave64 all-reduce through DPP / swizzle / permlane ---------------------------------------
+// After the call every lane of the wave holds the reduction.  Steps: xor 1 and xor 2 inside a
+// quad (quad_perm), then mirror inside 8 and 16 lanes (row_half_mirror, row_mirror; valid because
+// the earlier steps made each quad / half-row uniform), then swap 16-lane rows inside each half
+// (ds_swizzle) and finally the two halves (v_permlane32_swap via readlane-free builtin).
+template <int kCtrl>
+__device__ __forceinline__ float dpp_f32(float v) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), kCtrl, 0xF, 0xF, false));
+}
+__device__ __forceinline__ float swap_rows16_f32(float v) {
+  // ds_swizzle bit-mask mode: and_mask 0x1F, or_mask 0, xor_mask 0x10 -> lane ^ 16 within 32 lanes
+  return __int_as_float(__builtin_amdgcn_ds_swizzle(__float_as_int(v), 0x401F));
+}
+__device__ __forceinline__ float swap_halves_f32(float v) {
+  return __shfl_xor(v, 32, 64);
+}
+
+constexpr int kDppQuadXor1 = 0xB1;       // quad_perm [1,0,3,2]
+constexpr int kDppQuadXor2 = 0x4E;       // quad_perm [2,3,0,1]
+constexpr int kDppRowHalfMirror = 0x141;
+constexpr int kDppRowMirror = 0x140;
+
+__device__ __forceinline__ float wave_max(float v) {
+  v = fmaxf(v, dpp_f32<kDppQuadXor1>(v));
+  v = fmaxf(v, dpp_f32<kDppQuadXor2>(v));
+  v = fmaxf(v, dpp_f32<kDppRowHalfMirror>(v));
+  v = fmaxf(v, dpp_f32<kDppRowMirror>(v));
+  v = fmaxf(v, swap_rows16_f32(v));
+  v = fmaxf(v, swap_halves_f32(v));
+  return v;
+}
+
+template <int kCtrl>
+__device__ __forceinline__ double dpp_f64(double v) {
+  int lo = __double2loint(v), hi = __double2hiint(v);
+  lo = __builtin_amdgcn_update_dpp(0, lo, kCtrl, 0xF, 0xF, false);
+  hi = __builtin_amdgcn_update_dpp(0, hi, kCtrl, 0xF, 0xF, false);
+  return __hiloint2double(hi, lo);
+}
+__device__ __forceinline__ double swap_rows16_f64(double v) {
+  int lo = __builtin_amdgcn_ds_swizzle(__double2loint(v), 0x401F);
+  int hi = __builtin_amdgcn_ds_swizzle(__double2hiint(v), 0x401F);
+  return __hiloint2double(hi, lo);
+}
+
+__device__ __forceinline__ double wave_sum(double v) {
+  v += dpp_f64<kDppQuadXor1>(v);
+  v += dpp_f64<kDppQuadXor2>(v);
+  v += dpp_f64<kDppRowHalfMirror>(v);
+  v += dpp_f64<kDppRowMirror>(v);
+  v += swap_rows16_f64(v);
+  v += __shfl_xor(v, 32, 64);
+  return v;
+}
+
+// (score, index) argmax: larger score wins, equal scores go to the lower index.
+struct Best {
+  double s;
+  int32_t v;
+};
+__device__ __forceinline__ bool better(double s, int32_t v, const Best& o) {
+  return o.v < 0 || (v >= 0 && (s > o.s || (s == o.s && v < o.v)));
+}
+__device__ __forceinline__ Best wave_best(Best x) {
+#pragma unroll
+  for (int d = 1; d < kWave; d <<= 1) {
+    Best o;
+    o.s = __shfl_xor(x.s, d, 64);
+    o.v = __shfl_xor(x.v, d, 64);
+    if (better(o.s, o.v, x)) x = o;
+  }
+  return x;
+}
+
+}  // namespace ears

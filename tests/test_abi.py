@@ -1,0 +1,137 @@
+"""Host-only checks of the C ABI: the library loads, exports every symbol the header declares, and
+rejects bad arguments on the host before any GPU work (so these run without a GPU)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "ears.h")
+
+
+@pytest.fixture(scope="module")
+def L():
+    from paper_2512_13194_amd import binding, build
+    if build.is_stale():
+        build.build()
+    return binding.lib()
+
+
+def _declared_functions():
+    src = open(HEADER).read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    return sorted(set(re.findall(r"\b(ears_[a-z0-9_]+)\s*\(", src)))
+
+
+def test_header_symbols_are_exported(L):
+    names = _declared_functions()
+    assert "ears_verify_bf16" in names and "ears_verify_ex" in names and len(names) >= 11
+    for n in names:
+        assert hasattr(L, n), n
+
+
+def test_status_strings(L):
+    from paper_2512_13194_amd import binding
+    seen = {binding.status_string(i) for i in range(8)}
+    assert len(seen) == 8 and binding.status_string(0) == "ok"
+    assert binding.status_string(99) == "unknown status"
+
+
+def test_workspace_bytes(L):
+    from paper_2512_13194_amd import binding
+    w = binding.ears_workspace_bytes(2048, 256, 128256)
+    assert w >= 2048 * 2 * 16 and w % 256 == 0
+    assert binding.ears_workspace_bytes(4096, 256, 128256) > w
+    assert binding.ears_workspace_bytes(0, 1, 8) == 0
+    assert binding.ears_workspace_bytes(8, 0, 8) == 0
+    assert binding.ears_workspace_bytes(8, 1, 0) == 0
+    assert binding.ears_workspace_bytes(3, 4, 8) == 0      # fewer rows than sequences
+
+
+P = 0x10000   # a 256-byte aligned stand-in address; never dereferenced on these paths
+
+
+def _rect(L, fn="ears_verify_bf16", target=P, draft=P, tokens=P, B=2, K=3, V=64, T=1.0, beta=0.1,
+          seed=0, acc=P, out=P):
+    return getattr(L, fn)(target, draft, tokens, B, K, V, T, beta, seed, acc, out, None)
+
+
+def test_rect_argument_errors(L):
+    from paper_2512_13194_amd import binding as b
+    assert _rect(L, target=None) == b.EARS_ERR_NULL
+    assert _rect(L, draft=None) == b.EARS_ERR_NULL
+    assert _rect(L, tokens=None) == b.EARS_ERR_NULL
+    assert _rect(L, acc=None) == b.EARS_ERR_NULL
+    assert _rect(L, out=None) == b.EARS_ERR_NULL
+    for kw in (dict(B=0), dict(K=0), dict(V=0), dict(B=-1), dict(K=-5)):
+        assert _rect(L, **kw) == b.EARS_ERR_SHAPE, kw
+    for T in (0.0, -1.0, float("inf"), float("nan")):
+        assert _rect(L, T=T) == b.EARS_ERR_PARAM
+    for beta in (-0.1, float("inf"), float("nan")):
+        assert _rect(L, beta=beta) == b.EARS_ERR_PARAM
+    assert _rect(L, target=P + 8) == b.EARS_ERR_ALIGN
+    assert _rect(L, draft=P + 2) == b.EARS_ERR_ALIGN
+    assert _rect(L, tokens=P + 2) == b.EARS_ERR_ALIGN
+    assert _rect(L, fn="ears_verify_f32", out=P + 1) == b.EARS_ERR_ALIGN
+
+
+def _ex(L, dtype=1, target=P, draft=P, tokens=P, off=None, R=6, B=2, K=3, V=64, T=1.0, beta=0.1,
+        Ts=None, betas=None, seed=0, ids=None, ws=P, wsb=1 << 20, stages=7, acc=P, out=P,
+        stats=None, path=None, status=None):
+    return L.ears_verify_ex(dtype, target, draft, tokens, off, R, B, K, V, T, beta, Ts, betas, seed,
+                            ids, ws, wsb, stages, acc, out, stats, path, status, None)
+
+
+def test_ex_argument_errors(L):
+    from paper_2512_13194_amd import binding as b
+    assert _ex(L, dtype=2) == b.EARS_ERR_DTYPE
+    assert _ex(L, dtype=-1) == b.EARS_ERR_DTYPE
+    assert _ex(L, R=7) == b.EARS_ERR_SHAPE                 # rectangular: R must be B*K
+    assert _ex(L, off=P, R=1, B=2) == b.EARS_ERR_SHAPE     # ragged: at least one row per sequence
+    assert _ex(L, stages=0) == b.EARS_ERR_PARAM
+    assert _ex(L, stages=8) == b.EARS_ERR_PARAM
+    assert _ex(L, T=0.0) == b.EARS_ERR_PARAM
+    assert _ex(L, T=0.0, Ts=P, ws=None) == b.EARS_ERR_WORKSPACE   # per-sequence T: scalar ignored
+    assert _ex(L, ws=None) == b.EARS_ERR_WORKSPACE
+    assert _ex(L, wsb=16) == b.EARS_ERR_WORKSPACE
+    assert _ex(L, ws=P + 64) == b.EARS_ERR_ALIGN
+    assert _ex(L, off=P + 4, R=6) == b.EARS_ERR_ALIGN
+    assert _ex(L, ids=P + 4) == b.EARS_ERR_ALIGN
+    assert _ex(L, stats=P + 4) == b.EARS_ERR_ALIGN
+    need = b.ears_workspace_bytes(6, 2, 64)
+    assert _ex(L, wsb=need - 1) == b.EARS_ERR_WORKSPACE
+
+
+def test_ragged_argument_errors(L):
+    from paper_2512_13194_amd import binding as b
+    f = L.ears_verify_ragged_bf16
+    assert f(P, P, P, None, 6, 2, 64, P, P, 0, P, P, None) == b.EARS_ERR_NULL
+    assert f(P, P, P, P, 6, 2, 64, None, P, 0, P, P, None) == b.EARS_ERR_NULL
+    assert f(P, P, P, P, 6, 2, 64, P, None, 0, P, P, None) == b.EARS_ERR_NULL
+    assert f(P, P, P, P, 0, 2, 64, P, P, 0, P, P, None) == b.EARS_ERR_SHAPE
+    assert f(P, P, P, P, 6, 0, 64, P, P, 0, P, P, None) == b.EARS_ERR_SHAPE
+    assert f(P + 4, P, P, P, 6, 2, 64, P, P, 0, P, P, None) == b.EARS_ERR_ALIGN
+
+
+def test_bench_aid_argument_errors(L):
+    from paper_2512_13194_amd import binding as b
+    assert L.ears_bench_read(None, 1024, P, None) == b.EARS_ERR_NULL
+    assert L.ears_bench_read(P, 1000, P, None) == b.EARS_ERR_SHAPE
+    assert L.ears_bench_read(P + 8, 1024, P, None) == b.EARS_ERR_ALIGN
+    assert L.ears_bench_copy(P, None, 1024, None) == b.EARS_ERR_NULL
+    assert L.ears_bench_copy(P, P, 0, None) == b.EARS_ERR_SHAPE
+    assert L.ears_bench_read_sink_words() >= 256
+
+
+def test_binding_and_oracle_do_not_import_each_other():
+    pkg = os.path.join(ROOT, "paper_2512_13194_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".h", ".cpp")):
+                assert "oracle" not in open(os.path.join(dirpath, f)).read().replace(
+                    "the CPU oracle", "").replace("CPU oracle", ""), f
+    for f in os.listdir(os.path.join(ROOT, "oracle")):
+        if f.endswith((".py", ".c", ".h")):
+            src = open(os.path.join(ROOT, "oracle", f)).read()
+            assert "paper_2512_13194_amd" not in src and "hip" not in src.lower().replace("relationship", ""), f

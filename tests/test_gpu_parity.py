@@ -1,0 +1,240 @@
+"""GPU parity: the HIP library, called through its C ABI, against the CPU oracle on the same seeded
+inputs: the five workloads at full size, edge shapes, and the degenerate cases of the method."""
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from parity_util import ParityReport, compare
+
+pytestmark = pytest.mark.gpu
+
+NTHREADS = min(16, os.cpu_count() or 1)
+RTOL = {torch.float32: 1e-5, torch.bfloat16: 2e-3}
+
+
+@pytest.fixture(scope="module")
+def ears():
+    import paper_2512_13194_amd as pkg
+    pkg.lib()           # raises if libears.so has not been built: there is no fallback
+    assert torch.cuda.is_available()
+    return pkg
+
+
+def _log(msg):
+    print(msg, flush=True)
+
+
+def run_rect(ears, oracle, batch, T, beta, seed, seq_ids=None, check_simple=True):
+    from paper_2512_13194_amd import inputs
+    B, K, V = batch.B, batch.K, batch.V
+    ids_dev = None if seq_ids is None else torch.as_tensor(seq_ids, dtype=torch.int64, device="cuda")
+    out = ears.ears_verify_ex(batch.target, batch.draft, batch.tokens, temperature=T, beta=beta,
+                              seed=seed, seq_ids=ids_dev, want_stats=True, want_path=True)
+    torch.cuda.synchronize()
+    ora = oracle.verify(inputs.logits_to_numpy(batch.target), inputs.logits_to_numpy(batch.draft),
+                        batch.tokens.cpu().numpy(), T, beta, seed, seq_ids=seq_ids, nthreads=NTHREADS)
+    rep = compare(ora, out["accept_len"].cpu().numpy(), out["tokens"].cpu().numpy(),
+                  out["stats"].cpu().numpy(), out["path"].cpu().numpy(), None, K,
+                  RTOL[batch.target.dtype], batch.tokens.cpu().numpy(), V)
+    if check_simple and seq_ids is None:
+        fn = ears.ears_verify_f32 if batch.target.dtype == torch.float32 else ears.ears_verify_bf16
+        acc, tok = fn(batch.target, batch.draft, batch.tokens, T, beta, seed)
+        torch.cuda.synchronize()
+        assert torch.equal(acc, out["accept_len"])
+        assert torch.equal(tok.view(-1), out["tokens"])
+    return rep, ora, out
+
+
+def run_ragged(ears, oracle, batch, seed):
+    from paper_2512_13194_amd import inputs
+    out = ears.ears_verify_ex(batch.target, batch.draft, batch.tokens, row_offsets=batch.row_offsets,
+                              temperature_per_seq=batch.temperature, beta_per_seq=batch.beta,
+                              seed=seed, want_stats=True, want_path=True)
+    torch.cuda.synchronize()
+    off = batch.row_offsets.cpu().numpy()
+    ora = oracle.verify_ragged(inputs.logits_to_numpy(batch.target), inputs.logits_to_numpy(batch.draft),
+                               batch.tokens.cpu().numpy(), off, batch.temperature.cpu().numpy(),
+                               batch.beta.cpu().numpy(), seed, nthreads=NTHREADS)
+    rep = compare(ora, out["accept_len"].cpu().numpy(), out["tokens"].cpu().numpy(),
+                  out["stats"].cpu().numpy(), out["path"].cpu().numpy(), off, None,
+                  RTOL[batch.target.dtype], batch.tokens.cpu().numpy(), batch.V)
+    fn = ears.ears_verify_ragged_f32 if batch.target.dtype == torch.float32 else ears.ears_verify_ragged_bf16
+    acc, tok = fn(batch.target, batch.draft, batch.tokens, batch.row_offsets, batch.temperature,
+                  batch.beta, seed)
+    torch.cuda.synchronize()
+    assert torch.equal(acc, out["accept_len"]) and torch.equal(tok, out["tokens"])
+    return rep, ora, out
+
+
+# ------------------------------------------------------------------------ the five workloads
+@pytest.mark.parametrize("index", [0, 1, 2, 3])
+def test_workload_rect(ears, oracle, index):
+    from paper_2512_13194_amd import inputs
+    cfg = inputs.CONFIGS[index]
+    total = ParityReport()
+    for T in cfg["temperatures"]:
+        batch = inputs.make_config(index, T=T, device="cuda")
+        for beta in cfg["betas"]:
+            _log("workload %s T=%s beta=%s" % (cfg["name"], T, beta))
+            rep, ora, out = run_rect(ears, oracle, batch, T, beta, cfg["seed"])
+            _log("  " + rep.line() + " mean_accept=%.3f" % ora.accept_len.mean())
+            for f in ("exempt_decisions", "exempt_tokens", "sequences", "positions"):
+                setattr(total, f, getattr(total, f) + getattr(rep, f))
+        del batch
+        torch.cuda.empty_cache()
+    # exemptions must stay rare: the band is 1e-6 wide
+    assert total.exempt_decisions <= max(1, total.positions // 2000)
+    assert total.exempt_tokens <= max(1, total.sequences // 2000)
+
+
+def test_workload_ragged(ears, oracle):
+    from paper_2512_13194_amd import inputs
+    cfg = inputs.CONFIGS[4]
+    batch = inputs.make_config(4, device="cuda")
+    _log("workload %s rows=%d" % (cfg["name"], batch.total_draft_rows))
+    rep, ora, out = run_ragged(ears, oracle, batch, cfg["seed"])
+    _log("  " + rep.line() + " mean_accept=%.3f" % ora.accept_len.mean())
+    assert rep.exempt_decisions <= 3 and rep.exempt_tokens <= 2
+
+
+# ------------------------------------------------------------------------------- edge shapes
+@pytest.mark.parametrize("B,K,V,dtype", [
+    (1, 1, 1, torch.float32), (3, 2, 8, torch.float32), (5, 3, 13, torch.bfloat16),
+    (4, 1, 1003, torch.bfloat16), (2, 4, 4099, torch.float32), (7, 8, 8192, torch.bfloat16),
+    (3, 2, 8200, torch.bfloat16), (2, 3, 65537, torch.bfloat16), (33, 5, 2048, torch.float32),
+    (300, 2, 520, torch.bfloat16),
+])
+def test_edge_shapes(ears, oracle, B, K, V, dtype):
+    from paper_2512_13194_amd import inputs
+    _log("edge B=%d K=%d V=%d %s" % (B, K, V, dtype))
+    batch = inputs.make_rect(B, K, V, dtype, T=0.9, data_seed=B * 1000 + V, draft_noise=1.0,
+                             device="cuda")
+    for beta, seed in ((0.0, 5), (0.3, 6)):
+        rep, _, _ = run_rect(ears, oracle, batch, 0.9, beta, seed)
+        assert rep.exempt_decisions == 0 and rep.exempt_tokens == 0
+
+
+def test_masked_vocabulary_and_peaked_rows(ears, oracle):
+    from paper_2512_13194_amd import inputs
+    _log("masked / peaked")
+    batch = inputs.make_rect(16, 4, 5000, torch.bfloat16, T=1.0, data_seed=77, draft_noise=1.0,
+                             peaked_frac=0.3, peaked_sigma=12.0, device="cuda")
+    mask = torch.rand(5000, device="cuda") < 0.4
+    batch.target[:, :, mask] = float("-inf")
+    batch.draft[:, :, mask] = float("-inf")
+    batch.draft[0, :, :] = batch.target[0, :4, :]      # one sequence with identical rows
+    batch.tokens[0] = batch.target[0, :4].float().argmax(-1).to(torch.int32)
+    rep, ora, _ = run_rect(ears, oracle, batch, 1.0, 0.2, 9)
+    assert ora.accept_len[0] == 4
+    assert rep.exempt_decisions == 0 and rep.exempt_tokens == 0
+
+
+def test_identical_rows_accept_all_and_bonus(ears, oracle):
+    from paper_2512_13194_amd import inputs
+    _log("identical rows")
+    batch = inputs.make_rect(20, 5, 3000, torch.float32, T=0.7, data_seed=78, device="cuda")
+    batch.draft.copy_(batch.target[:, :5, :])
+    rep, ora, out = run_rect(ears, oracle, batch, 0.7, 0.0, 10)
+    assert np.all(ora.accept_len == 5) and torch.all(out["accept_len"] == 5)
+    assert rep.exempt_tokens == 0
+
+
+def test_empty_residual_fallback_and_bad_token(ears, oracle):
+    from paper_2512_13194_amd import inputs
+    _log("empty residual / out-of-range token")
+    batch = inputs.make_rect(8, 3, 700, torch.float32, T=1.0, data_seed=79, device="cuda")
+    batch.draft.copy_(batch.target[:, :3, :])
+    # sequence 0: identical rows and a draft token whose probability is below the division
+    # guard -> rejected with an empty residual -> fallback to the target distribution
+    batch.target[0, 1, 5] = float("-inf")
+    batch.draft[0, 1, 5] = float("-inf")
+    batch.tokens[0, 1] = 5
+    # sequence 1: out-of-range token
+    batch.tokens[1, 2] = 700
+    batch.tokens[2, 0] = -3
+    status = torch.zeros(1, dtype=torch.int32, device="cuda")
+    out = ears.ears_verify_ex(batch.target, batch.draft, batch.tokens, temperature=1.0, beta=0.0,
+                              seed=11, want_stats=True, want_path=True, status_word=status)
+    torch.cuda.synchronize()
+    ora = oracle.verify(inputs.logits_to_numpy(batch.target), inputs.logits_to_numpy(batch.draft),
+                        batch.tokens.cpu().numpy(), 1.0, 0.0, 11)
+    assert ora.status == 1 and int(status.item()) & 1 == 1
+    assert ora.samp[0, 3] == 2.0 and ora.accept_len[0] == 1
+    assert ora.accept_len[1] == 2 and ora.accept_len[2] == 0
+    rep = compare(ora, out["accept_len"].cpu().numpy(), out["tokens"].cpu().numpy(),
+                  out["stats"].cpu().numpy(), out["path"].cpu().numpy(), None, 3, 1e-5,
+                  batch.tokens.cpu().numpy(), 700)
+    assert rep.exempt_decisions == 0 and rep.exempt_tokens == 0
+
+
+def test_seq_ids_batch_order_invariance_and_determinism(ears, oracle):
+    from paper_2512_13194_amd import inputs
+    _log("seq ids / determinism")
+    batch = inputs.make_rect(40, 4, 4000, torch.bfloat16, T=1.0, data_seed=80, draft_noise=1.0,
+                             device="cuda")
+    ids = (np.random.default_rng(1).permutation(100000)[:40] + (1 << 41)).astype(np.int64)
+    rep, ora, out = run_rect(ears, oracle, batch, 1.0, 0.25, 12, seq_ids=ids)
+    assert rep.exempt_decisions == 0 and rep.exempt_tokens == 0
+    out2 = ears.ears_verify_ex(batch.target, batch.draft, batch.tokens, temperature=1.0, beta=0.25,
+                               seed=12, seq_ids=torch.as_tensor(ids, device="cuda"))
+    torch.cuda.synchronize()
+    assert torch.equal(out2["tokens"], out["tokens"]) and torch.equal(out2["accept_len"], out["accept_len"])
+    perm = torch.randperm(40, generator=torch.Generator().manual_seed(3)).cuda()
+    out3 = ears.ears_verify_ex(batch.target[perm].contiguous(), batch.draft[perm].contiguous(),
+                               batch.tokens[perm].contiguous(), temperature=1.0, beta=0.25, seed=12,
+                               seq_ids=torch.as_tensor(ids, device="cuda")[perm].contiguous())
+    torch.cuda.synchronize()
+    assert torch.equal(out3["accept_len"], out["accept_len"][perm])
+    assert torch.equal(out3["tokens"].view(40, 5), out["tokens"].view(40, 5)[perm])
+
+
+def test_stages_split_reuses_cached_statistics(ears, oracle):
+    from paper_2512_13194_amd import inputs
+    _log("stages")
+    batch = inputs.make_rect(12, 3, 6000, torch.bfloat16, T=0.8, data_seed=81, draft_noise=1.0,
+                             device="cuda")
+    full = ears.ears_verify_ex(batch.target, batch.draft, batch.tokens, temperature=0.8, beta=0.3, seed=13)
+    a = ears.ears_verify_ex(batch.target, batch.draft, batch.tokens, temperature=0.8, beta=0.3, seed=13,
+                            stages=ears.EARS_STAGE_STATS)
+    b = ears.ears_verify_ex(batch.target, batch.draft, batch.tokens, temperature=0.8, beta=0.3, seed=13,
+                            stages=ears.EARS_STAGE_DECIDE, workspace=a["workspace"])
+    n_only = b["tokens"].clone()
+    c = ears.ears_verify_ex(batch.target, batch.draft, batch.tokens, temperature=0.8, beta=0.3, seed=13,
+                            stages=ears.EARS_STAGE_SAMPLE, workspace=a["workspace"],
+                            out_accept_len=b["accept_len"], out_tokens=b["tokens"])
+    torch.cuda.synchronize()
+    assert torch.equal(c["accept_len"], full["accept_len"]) and torch.equal(c["tokens"], full["tokens"])
+    # after DECIDE alone the slot of the replacement token is still -1
+    acc = full["accept_len"].cpu().numpy()
+    t = n_only.view(12, 4).cpu().numpy()
+    assert all(t[i, acc[i]] == -1 for i in range(12))
+
+
+def test_ragged_small(ears, oracle):
+    from paper_2512_13194_amd import inputs
+    _log("ragged small")
+    for dtype, V in ((torch.bfloat16, 3001), (torch.float32, 512)):
+        batch = inputs.make_ragged(37, V, dtype, data_seed=82, device="cuda")
+        rep, _, _ = run_ragged(ears, oracle, batch, 14)
+        assert rep.exempt_decisions == 0 and rep.exempt_tokens == 0
+
+
+def test_output_law_on_gpu(ears):
+    """V = 8, K = 1, beta = 0: the emitted token follows P_target (chi-square), on the GPU path."""
+    from scipy import stats
+    _log("output law on GPU")
+    g = torch.Generator().manual_seed(5)
+    V, N, T = 8, 200000, 1.0
+    lt = torch.randn(V, generator=g) * 1.5
+    ld = lt + 0.9 * torch.randn(V, generator=g)
+    pt = torch.softmax(lt.double() / T, 0).numpy()
+    pd = torch.softmax(ld.double() / T, 0)
+    tokens = torch.multinomial(pd.float(), N, replacement=True, generator=g).to(torch.int32).view(N, 1).cuda()
+    target = lt.expand(N, 2, V).contiguous().cuda()
+    draft = ld.expand(N, 1, V).contiguous().cuda()
+    acc, tok = ears.ears_verify_f32(target, draft, tokens, T, 0.0, 4242)
+    torch.cuda.synchronize()
+    obs = np.bincount(tok[:, 0].cpu().numpy(), minlength=V)
+    assert stats.chisquare(obs, pt * N).pvalue > 1e-4
