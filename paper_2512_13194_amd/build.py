@@ -16,6 +16,9 @@ HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
     # packed-fp32 instructions are kept out of the generated code
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    # no implicit mul+add fusion: the kernels rely on fl(m*c) being the rounded product and
+    # write fmaf() where a fused operation is wanted
+    "-ffp-contract=off",
     "-Wall", "-Wextra", "-Wno-unused-parameter",
 ]
 

@@ -17,6 +17,10 @@
 #include "../../include/ears.h"
 #include "ears_device.h"
 
+// Products such as fl(m*c) must stay rounded products (their rounding is undone explicitly
+// later); fused operations are written as fmaf().
+#pragma clang fp contract(off)
+
 namespace ears {
 
 constexpr double kLog2e = 1.4426950408889634074;

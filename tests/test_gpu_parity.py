@@ -33,8 +33,10 @@ def run_rect(ears, oracle, batch, T, beta, seed, seq_ids=None, check_simple=True
     out = ears.ears_verify_ex(batch.target, batch.draft, batch.tokens, temperature=T, beta=beta,
                               seed=seed, seq_ids=ids_dev, want_stats=True, want_path=True)
     torch.cuda.synchronize()
+    # the ABI takes temperature and beta as float32: the oracle gets exactly those values
     ora = oracle.verify(inputs.logits_to_numpy(batch.target), inputs.logits_to_numpy(batch.draft),
-                        batch.tokens.cpu().numpy(), T, beta, seed, seq_ids=seq_ids, nthreads=NTHREADS)
+                        batch.tokens.cpu().numpy(), float(np.float32(T)), float(np.float32(beta)),
+                        seed, seq_ids=seq_ids, nthreads=NTHREADS)
     rep = compare(ora, out["accept_len"].cpu().numpy(), out["tokens"].cpu().numpy(),
                   out["stats"].cpu().numpy(), out["path"].cpu().numpy(), None, K,
                   RTOL[batch.target.dtype], batch.tokens.cpu().numpy(), V)
