@@ -30,7 +30,7 @@ def log(*a):
 
 def kernel_source_hash() -> str:
     h = hashlib.sha256()
-    for rel in ("paper_2512_13194_amd/csrc/ears_kernels.hip", "paper_2512_13194_amd/csrc/ears_device.h"):
+    for rel in ("paper_2512_13194_amd/csrc/row_stats.h", "paper_2512_13194_amd/csrc/ears_device.h"):
         with open(os.path.join(ROOT, rel), "rb") as f:
             h.update(f.read())
     return h.hexdigest()[:16]

@@ -9,8 +9,9 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(_HERE, "csrc")
 LIB = os.path.join(_HERE, "libears.so")
 SOURCES = [os.path.join(CSRC, "ears_kernels.hip")]
-HEADERS = [os.path.join(CSRC, "ears_device.h"),
-           os.path.join(os.path.dirname(_HERE), "include", "ears.h")]
+HEADERS = [os.path.join(CSRC, h) for h in ("ears_device.h", "row_stats.h", "decide.h", "sample.h",
+                                            "bench_aids.h")]
+HEADERS.append(os.path.join(os.path.dirname(_HERE), "include", "ears.h"))
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

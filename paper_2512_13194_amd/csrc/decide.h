@@ -1,0 +1,76 @@
+// Stage DECIDE of the EARS verification step: ratio, uniform, tolerance, threshold, the three-way
+// decision of the paper's Section 3.2 (steps 2-5) with the guards of Section 3.3 item 2, and the
+// first-rejection scan of Section 3.1.
+#pragma once
+
+#include "ears_device.h"
+
+namespace ears {
+
+// One wave decides one sequence: lane i handles draft position i (positions beyond 64 in further
+// rounds); a ballot of the rejecting lanes gives the first rejection.  The B*K decision scalars
+// are evaluated in fp64 from the cached row statistics (row maximum m, Z = sum exp((l-m)/T) and
+// the draft token's logit), so the decision does not depend on fp32 rounding of R or the
+// threshold.  Returns the accept length n in every lane.  With write_outputs the wave also stores
+// the accept length, the accepted prefix and the -1 tail of out_tokens (slot n is left for the
+// sampling stage), and the optional per-position statistics / branch ids.
+__device__ __forceinline__ int decide_sequence(const Problem& p, int b, int lane, bool write_outputs) {
+  const int64_t r0 = seq_row_begin(p, b);
+  const int Kb = seq_len(p, b);
+  const double T = (double)seq_temperature(p, b);
+  const double beta = (double)seq_beta(p, b);
+  const uint64_t seq = seq_rng_id(p, b);
+  int n = Kb;
+  bool bad_token = false;
+  for (int base = 0; base < Kb; base += kWave) {
+    if (n < Kb && !write_outputs) break;  // later positions cannot change n
+    const int i = base + lane;
+    int decision = 1;
+    if (i < Kb) {
+      const int64_t r = r0 + i;
+      const double mt = (double)p.m[2 * r], Zt = p.Z[2 * r], lxt = (double)p.lx[2 * r];
+      const double md = (double)p.m[2 * r + 1], Zd = p.Z[2 * r + 1], lxd = (double)p.lx[2 * r + 1];
+      const int32_t x = p.tokens[r];
+      const bool valid = x >= 0 && x < p.V;
+      const double Ptx = valid ? exp((lxt - mt) / T) / Zt : 0.0;
+      const double Pdx = valid ? exp((lxd - md) / T) / Zd : 0.0;
+      const double R = Ptx / fmax(Pdx, kEpsilon);               // step 2 with the division guard
+      const double U = accept_uniform(p.seed, seq, (uint32_t)i);  // step 3
+      const double unc = 1.0 - 1.0 / Zt;                        // 1 - max P_t; max P_t = 1/Z_t
+      const double tol = beta * unc;                            // step 4
+      const double thr = fmax(U - tol, 0.0);                    // threshold clamp
+      if (!valid) { decision = 0; bad_token = true; }           // step 5
+      else if (R >= U) decision = 1;
+      else if (R >= thr) decision = 2;
+      else decision = 0;
+      if (write_outputs && p.out_stats) {
+        double* d = p.out_stats + r * EARS_NSTATS;
+        d[0] = mt; d[1] = Zt; d[2] = Ptx; d[3] = md; d[4] = Zd; d[5] = Pdx;
+        d[6] = unc; d[7] = R; d[8] = U; d[9] = thr;
+      }
+      if (write_outputs && p.out_path) p.out_path[r] = decision;
+    }
+    const unsigned long long rejecting = __ballot(decision == 0);
+    if (rejecting != 0ull && n == Kb) n = base + (__ffsll((long long)rejecting) - 1);
+  }
+  if (write_outputs) {
+    if (lane == 0) p.accept_len[b] = n;
+    int32_t* out = p.out_tokens + r0 + b;
+    for (int i = lane; i <= Kb; i += kWave)
+      if (i != n) out[i] = i < n ? p.tokens[r0 + i] : -1;
+    if (p.status_word && __ballot(bad_token) != 0ull && lane == 0) atomicOr(p.status_word, 1u);
+  }
+  return n;
+}
+
+// Stand-alone decision stage: four sequences per workgroup, one per wave.  Slot n of out_tokens
+// is set to -1 here; the sampling stage overwrites it.
+__global__ __launch_bounds__(kBlock) void decide_kernel(Problem p) {
+  const int lane = (int)threadIdx.x & (kWave - 1);
+  const int b = (int)blockIdx.x * kWavesPerBlock + (int)threadIdx.x / kWave;
+  if (b >= p.B) return;
+  const int n = decide_sequence(p, b, lane, true);
+  if (lane == 0) p.out_tokens[seq_row_begin(p, b) + b + n] = -1;
+}
+
+}  // namespace ears

@@ -10,6 +10,16 @@ constexpr int kWave = 64;
 constexpr int kBlock = 256;             // threads per workgroup: 4 waves
 constexpr int kWavesPerBlock = kBlock / kWave;
 
+constexpr double kLog2e = 1.4426950408889634074;
+constexpr double kEpsilon = 1e-10;      // division guard of the paper's Section 3.3 item 2
+
+// Sampling stage: each workgroup filters one chunk of a row and leaves a record of
+// kRecordWords 32-bit words: [0] threshold (float bits), [1] survivor count or kRecordOverflow,
+// then kRecordCap pairs (vocabulary index, upper score bound as float bits).
+constexpr int kRecordCap = 48;
+constexpr int kRecordWords = 2 + 2 * kRecordCap + 2;
+constexpr int kRecordOverflow = -1;
+
 // Everything a kernel needs to locate its rows.  Rectangular batches have row_offsets == nullptr:
 // sequence b then owns draft rows b*K .. b*K+K-1.  In both layouts draft row r of sequence b
 // pairs with target row r + b (every earlier sequence has one extra, "bonus", target row).
@@ -32,6 +42,12 @@ struct Problem {
   double* Z;
   float* m;
   float* lx;
+  // sampling stage scratch: per-sequence arrival counters and per-chunk records
+  uint32_t* arrivals;   // [B]
+  uint32_t* records;    // [B, S, kRecordWords]
+  int S;                // chunks per row
+  int chunk;            // vocabulary entries per chunk (a multiple of the tile size)
+  int decide_fused;     // the sampling kernel runs the decision scan itself
   // outputs
   int32_t* accept_len;
   int32_t* out_tokens;

@@ -4,7 +4,8 @@
 //                                       Section 3.3 item 1: max P_t cached, never re-scanned)
 //   stage DECIDE : decide_kernel      - ratio, uniform, tolerance, threshold, three-way decision,
 //                                       first-rejection scan (Section 3.2 steps 2-5, Section 3.1)
-//   stage SAMPLE : sample_kernel      - residual / bonus token by Gumbel-max at slot n
+//   stage SAMPLE : sample_kernel      - residual / bonus token by Gumbel-max at slot n; when DECIDE
+//                                       and SAMPLE run in one call the scan runs in its prologue
 //
 // The path is bound by HBM bandwidth (every needed row is read once, plus one re-read of the row
 // pair the sampler needs), so there is no matrix-core work here.
@@ -15,7 +16,11 @@
 #include <mutex>
 
 #include "../../include/ears.h"
+#include "bench_aids.h"
+#include "decide.h"
 #include "ears_device.h"
+#include "row_stats.h"
+#include "sample.h"
 
 // Products such as fl(m*c) must stay rounded products (their rounding is undone explicitly
 // later); fused operations are written as fmaf().
@@ -23,288 +28,44 @@
 
 namespace ears {
 
-constexpr double kLog2e = 1.4426950408889634074;
-constexpr double kEpsilon = 1e-10;  // division guard of Section 3.3 item 2
-
-// =================================================================================================
-// Stage STATS.  One workgroup per logit row; workgroup 2r handles the target row paired with draft
-// row r, workgroup 2r+1 the draft row itself.
-//
-// Each lane keeps a running maximum m and S = sum exp2(l*c - fl(m*c)), c = log2(e)/T, over the
-// elements it has seen.  A chunk of register-resident elements is first reduced to its maximum,
-// so the running maximum changes (and S is rescaled) at most once per chunk and the inner loop
-// is one FMA, one v_exp_f32 and one add per element.  The lanes are merged with the associative
-// rule (m,S) + (m',S') = (M, S*2^(mc-Mc) + S'*2^(m'c-Mc)), M = max(m,m'): a DPP wave reduction of
-// the maxima, a per-lane rescale, an fp64 DPP wave sum, and an LDS combine of the four waves.
-// The rounding of fl(M*c) is removed exactly at the end in fp64, so Z = sum exp((l - M)/T) carries
-// only the fp32 rounding of the individual terms.  max P = 1/Z needs no second pass.
-// =================================================================================================
-template <int N>
-__device__ __forceinline__ void accumulate(const float (&f)[N], float c, float& m_run, float& mc,
-                                           float& S) {
-  float cm = f[0];
-#pragma unroll
-  for (int j = 1; j < N; ++j) cm = fmaxf(cm, f[j]);
-  if (cm > m_run) {
-    const float mc_new = cm * c;
-    S = (m_run == -INFINITY) ? 0.0f : S * __builtin_amdgcn_exp2f(mc - mc_new);
-    m_run = cm;
-    mc = mc_new;
-  }
-  float s[4] = {0.0f, 0.0f, 0.0f, 0.0f};
-#pragma unroll
-  for (int j = 0; j < N; ++j) s[j & 3] += __builtin_amdgcn_exp2f(fmaf(f[j], c, -mc));
-  S += (s[0] + s[1]) + (s[2] + s[3]);
-}
-
-template <typename DT, int kUnroll>
-__global__ __launch_bounds__(kBlock) void row_stats_kernel(Problem p) {
-  const int64_t r = (int64_t)(blockIdx.x >> 1);
-  const int which = (int)(blockIdx.x & 1u);
-  const int b = seq_of_row(p, r);
-  const int64_t row = which == 0 ? r + b : r;
-  const typename DT::storage* base =
-      static_cast<const typename DT::storage*>(which == 0 ? p.target : p.draft) + row * (int64_t)p.V;
-  const int V = p.V;
-  const int tid = (int)threadIdx.x;
-  const float c = (float)(kLog2e / (double)seq_temperature(p, b));
-
-  float m_run = -INFINITY, mc = 0.0f, S = 0.0f;
-
-  // scalar head up to the first 16-byte boundary (empty when rows are 16-byte multiples)
-  constexpr int kPer = DT::kPerVec;
-  const uintptr_t addr = reinterpret_cast<uintptr_t>(base);
-  int head = (int)(((16u - (addr & 15u)) & 15u) / sizeof(typename DT::storage));
-  if (head > V) head = V;
-  const int nvec = (V - head) / kPer;
-  const int tail0 = head + nvec * kPer;
-  const int ntail = V - tail0;
-  if (tid < head + ntail) {
-    float f[1] = {DT::load(base, tid < head ? tid : tail0 + (tid - head))};
-    accumulate<1>(f, c, m_run, mc, S);
-  }
-
-  const uint4* vp = reinterpret_cast<const uint4*>(base + head);
-  for (int i0 = tid; i0 < nvec; i0 += kBlock * kUnroll) {
-    uint4 raw[kUnroll];
-#pragma unroll
-    for (int u = 0; u < kUnroll; ++u) {
-      const int i = i0 + u * kBlock;
-      raw[u] = i < nvec ? vp[i] : DT::neg_inf_vec();
-    }
-    float f[kUnroll * kPer];
-#pragma unroll
-    for (int u = 0; u < kUnroll; ++u) {
-      float g[kPer];
-      DT::unpack(raw[u], g);
-#pragma unroll
-      for (int j = 0; j < kPer; ++j) f[u * kPer + j] = g[j];
-    }
-    accumulate<kUnroll * kPer>(f, c, m_run, mc, S);
-  }
-
-  // merge the 256 lanes
-  __shared__ float sh_m[kWavesPerBlock];
-  __shared__ double sh_s[kWavesPerBlock];
-  const int lane = tid & (kWave - 1), wave = tid / kWave;
-  const float wm = wave_max(m_run);
-  if (lane == 0) sh_m[wave] = wm;
-  __syncthreads();
-  float M = sh_m[0];
-#pragma unroll
-  for (int w = 1; w < kWavesPerBlock; ++w) M = fmaxf(M, sh_m[w]);
-  const float Mc = M * c;
-  const float scale = (m_run == -INFINITY) ? 0.0f : __builtin_amdgcn_exp2f(mc - Mc);
-  const double part = wave_sum((double)S * (double)scale);
-  if (lane == 0) sh_s[wave] = part;
-  __syncthreads();
-  if (tid == 0) {
-    double Zp = 0.0;
-#pragma unroll
-    for (int w = 0; w < kWavesPerBlock; ++w) Zp += sh_s[w];
-    // the lanes used fl(M*c) as the offset; undo its rounding exactly
-    const double Z = Zp * exp2((double)Mc - (double)M * (double)c);
-    const int32_t x = p.tokens[r];
-    const int64_t slot = 2 * r + which;
-    p.Z[slot] = Z;
-    p.m[slot] = M;
-    p.lx[slot] = (x >= 0 && x < V) ? DT::load(base, x) : -INFINITY;
-  }
-}
-
-// =================================================================================================
-// Stage DECIDE.  One thread per sequence, fp64: the B*K decision scalars are cheap, and the
-// decision must not depend on fp32 rounding of R or the threshold.
-// =================================================================================================
-__global__ __launch_bounds__(kBlock) void decide_kernel(Problem p) {
-  const int b = (int)(blockIdx.x * blockDim.x + threadIdx.x);
-  if (b >= p.B) return;
-  const int64_t r0 = seq_row_begin(p, b);
-  const int Kb = seq_len(p, b);
-  const double T = (double)seq_temperature(p, b);
-  const double beta = (double)seq_beta(p, b);
-  const uint64_t seq = seq_rng_id(p, b);
-  int n = Kb;
-  bool bad_token = false;
-  for (int i = 0; i < Kb; ++i) {
-    const int64_t r = r0 + i;
-    const double mt = (double)p.m[2 * r], Zt = p.Z[2 * r], lxt = (double)p.lx[2 * r];
-    const double md = (double)p.m[2 * r + 1], Zd = p.Z[2 * r + 1], lxd = (double)p.lx[2 * r + 1];
-    const int32_t x = p.tokens[r];
-    const bool valid = x >= 0 && x < p.V;
-    const double Ptx = valid ? exp((lxt - mt) / T) / Zt : 0.0;
-    const double Pdx = valid ? exp((lxd - md) / T) / Zd : 0.0;
-    const double R = Ptx / fmax(Pdx, kEpsilon);            // Section 3.2 step 2, guard 3.3 item 2
-    const double U = accept_uniform(p.seed, seq, (uint32_t)i);  // step 3
-    const double unc = 1.0 - 1.0 / Zt;                     // 1 - max P_t, max P_t = 1/Z_t
-    const double tol = beta * unc;                         // step 4
-    const double thr = fmax(U - tol, 0.0);                 // threshold clamp, 3.3 item 2
-    int decision;                                          // step 5
-    if (!valid) { decision = 0; bad_token = true; }
-    else if (R >= U) decision = 1;
-    else if (R >= thr) decision = 2;
-    else decision = 0;
-    if (decision == 0 && n == Kb) n = i;                   // first rejection (Section 3.1)
-    if (p.out_stats) {
-      double* d = p.out_stats + r * EARS_NSTATS;
-      d[0] = mt; d[1] = Zt; d[2] = Ptx; d[3] = md; d[4] = Zd; d[5] = Pdx;
-      d[6] = unc; d[7] = R; d[8] = U; d[9] = thr;
-    }
-    if (p.out_path) p.out_path[r] = decision;
-  }
-  p.accept_len[b] = n;
-  int32_t* out = p.out_tokens + r0 + b;
-  for (int i = 0; i <= Kb; ++i) out[i] = i < n ? p.tokens[r0 + i] : -1;
-  if (bad_token && p.status_word) atomicOr(p.status_word, 1u);
-}
-
-// =================================================================================================
-// Stage SAMPLE.  One workgroup per sequence; scores in fp64 exactly as defined:
-//   residual (n < K): log(max(0, p_t(v) - p_d(v))) + g(v) over rows n, with the cached (m, Z);
-//   bonus    (n = K): l_t[K, v] / T + g(v);
-//   empty residual  : log p_t(v) + g(v).
-// g(v) = -log(-log u(v)), u from Philox keyed (seed, seq, n, v).
-// =================================================================================================
-__device__ __forceinline__ double gumbel64(uint64_t seed, uint64_t seq, uint32_t pos, uint32_t v) {
-  const Philox blk = noise_block(seed, seq, pos, 1u, v >> 2);
-  const uint32_t w = (v & 2u) ? ((v & 1u) ? blk.w[3] : blk.w[2]) : ((v & 1u) ? blk.w[1] : blk.w[0]);
-  const double u = (double)(w >> 9) * 0x1p-23 + 0x1p-24;
-  return -log(-log(u));
-}
-
-__device__ Best block_best(Best x) {
-  __shared__ double sh_s[kWavesPerBlock];
-  __shared__ int32_t sh_v[kWavesPerBlock];
-  x = wave_best(x);
-  const int lane = (int)threadIdx.x & (kWave - 1), wave = (int)threadIdx.x / kWave;
-  __syncthreads();
-  if (lane == 0) { sh_s[wave] = x.s; sh_v[wave] = x.v; }
-  __syncthreads();
-  Best r{sh_s[0], sh_v[0]};
-#pragma unroll
-  for (int w = 1; w < kWavesPerBlock; ++w)
-    if (better(sh_s[w], sh_v[w], r)) r = Best{sh_s[w], sh_v[w]};
-  return r;
-}
-
-template <typename DT>
-__global__ __launch_bounds__(kBlock) void sample_kernel(Problem p) {
-  const int b = (int)blockIdx.x;
-  const int64_t r0 = seq_row_begin(p, b);
-  const int Kb = seq_len(p, b);
-  const int n = p.accept_len[b];
-  const double T = (double)seq_temperature(p, b);
-  const uint64_t seq = seq_rng_id(p, b);
-  const int V = p.V;
-  const typename DT::storage* trow =
-      static_cast<const typename DT::storage*>(p.target) + (r0 + b + n) * (int64_t)V;
-  Best best{-INFINITY, -1};
-  if (n < Kb) {
-    const int64_t r = r0 + n;
-    const typename DT::storage* drow =
-        static_cast<const typename DT::storage*>(p.draft) + r * (int64_t)V;
-    const double mt = (double)p.m[2 * r], Zt = p.Z[2 * r];
-    const double md = (double)p.m[2 * r + 1], Zd = p.Z[2 * r + 1];
-    for (int v = (int)threadIdx.x; v < V; v += kBlock) {
-      const double pt = exp(((double)DT::load(trow, v) - mt) / T) / Zt;
-      const double pd = exp(((double)DT::load(drow, v) - md) / T) / Zd;
-      const double q = pt - pd;
-      if (q > 0.0) {
-        const double s = log(q) + gumbel64(p.seed, seq, (uint32_t)n, (uint32_t)v);
-        if (better(s, v, best)) best = Best{s, v};
-      }
-    }
-    best = block_best(best);
-    if (best.v < 0) {  // empty residual: draw from the target distribution of this position
-      for (int v = (int)threadIdx.x; v < V; v += kBlock) {
-        const double pt = exp(((double)DT::load(trow, v) - mt) / T) / Zt;
-        if (pt > 0.0) {
-          const double s = log(pt) + gumbel64(p.seed, seq, (uint32_t)n, (uint32_t)v);
-          if (better(s, v, best)) best = Best{s, v};
-        }
-      }
-      best = block_best(best);
-    }
-  } else {
-    for (int v = (int)threadIdx.x; v < V; v += kBlock) {
-      const double l = (double)DT::load(trow, v);
-      if (l > -INFINITY) {
-        const double s = l / T + gumbel64(p.seed, seq, (uint32_t)n, (uint32_t)v);
-        if (better(s, v, best)) best = Best{s, v};
-      }
-    }
-    best = block_best(best);
-  }
-  if (threadIdx.x == 0) p.out_tokens[r0 + b + n] = best.v;
-}
-
-// =================================================================================================
-// Measurement aids.
-// =================================================================================================
-constexpr int kBenchBlocks = 4096;
-
-__global__ __launch_bounds__(kBlock) void bench_read_kernel(const uint4* src, size_t nvec,
-                                                            uint32_t* sink) {
-  uint32_t acc = 0;
-  const size_t stride = (size_t)gridDim.x * kBlock;
-  size_t i = (size_t)blockIdx.x * kBlock + threadIdx.x;
-  for (; i + 3 * stride < nvec; i += 4 * stride) {
-    const uint4 a = src[i], b = src[i + stride], c = src[i + 2 * stride], d = src[i + 3 * stride];
-    acc ^= a.x ^ a.y ^ a.z ^ a.w ^ b.x ^ b.y ^ b.z ^ b.w ^ c.x ^ c.y ^ c.z ^ c.w ^ d.x ^ d.y ^ d.z ^ d.w;
-  }
-  for (; i < nvec; i += stride) {
-    const uint4 a = src[i];
-    acc ^= a.x ^ a.y ^ a.z ^ a.w;
-  }
-#pragma unroll
-  for (int d = 1; d < kWave; d <<= 1) acc ^= __shfl_xor(acc, d, 64);
-  __shared__ uint32_t sh[kWavesPerBlock];
-  if ((threadIdx.x & (kWave - 1)) == 0) sh[threadIdx.x / kWave] = acc;
-  __syncthreads();
-  if (threadIdx.x == 0) sink[blockIdx.x] = sh[0] ^ sh[1] ^ sh[2] ^ sh[3];
-}
-
-__global__ __launch_bounds__(kBlock) void bench_copy_kernel(uint4* dst, const uint4* src,
-                                                            size_t nvec) {
-  const size_t stride = (size_t)gridDim.x * kBlock;
-  for (size_t i = (size_t)blockIdx.x * kBlock + threadIdx.x; i < nvec; i += stride) dst[i] = src[i];
-}
-
 // =================================================================================================
 // Host side.
 // =================================================================================================
 struct WorkspaceLayout {
-  size_t off_Z, off_m, off_lx, total;
+  size_t off_Z, off_m, off_lx, off_arrivals, off_records, total;
+  int S, chunk;  // how the sampling stage splits a row
 };
 
 static size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
+// The sampling stage touches only B rows, so each row is split into S chunks of whole tiles
+// (one tile = one 16-byte load per thread of a workgroup) until about kSampleTargetGroups
+// workgroups exist: enough waves per CU to overlap the row reads with the Philox arithmetic.
+constexpr int kSampleTargetGroups = 1024;
+
+static void sample_split(int B, int V, int elems_per_tile, int* S, int* chunk) {
+  const int ntiles = (V + elems_per_tile - 1) / elems_per_tile;
+  int want = (kSampleTargetGroups + B - 1) / B;
+  if (want < 1) want = 1;
+  if (want > ntiles) want = ntiles;
+  const int tiles_per_chunk = (ntiles + want - 1) / want;
+  *chunk = tiles_per_chunk * elems_per_tile;
+  *S = (V + *chunk - 1) / *chunk;
+}
+
 static bool workspace_layout(int64_t R, int B, int V, WorkspaceLayout* w) {
   if (R < 1 || B < 1 || V < 1 || R < B || R > (int64_t)0x3FFFFFFF) return false;
+  // records are sized for whichever of the two tilings (4 or 8 elements per 16 bytes) splits finer
+  int S4, S8, chunk;
+  sample_split(B, V, kBlock * 4, &S4, &chunk);
+  sample_split(B, V, kBlock * 8, &S8, &chunk);
+  if (S8 > S4) S4 = S8;
   size_t o = 0;
-  w->off_Z = o;  o = align_up(o + (size_t)(2 * R) * sizeof(double), 256);
-  w->off_m = o;  o = align_up(o + (size_t)(2 * R) * sizeof(float), 256);
-  w->off_lx = o; o = align_up(o + (size_t)(2 * R) * sizeof(float), 256);
+  w->off_Z = o;        o = align_up(o + (size_t)(2 * R) * sizeof(double), 256);
+  w->off_m = o;        o = align_up(o + (size_t)(2 * R) * sizeof(float), 256);
+  w->off_lx = o;       o = align_up(o + (size_t)(2 * R) * sizeof(float), 256);
+  w->off_arrivals = o; o = align_up(o + (size_t)B * sizeof(uint32_t), 256);
+  w->off_records = o;  o = align_up(o + (size_t)B * S4 * kRecordWords * sizeof(uint32_t), 256);
   w->total = o;
   return true;
 }
@@ -339,16 +100,26 @@ static int validate(int dtype, const void* target, const void* draft, const int3
 }
 
 template <typename DT>
-static int launch(const Problem& p, int stages, hipStream_t stream) {
-  if (stages & EARS_STAGE_STATS) {
+static int launch(Problem p, int stages, hipStream_t stream) {
+  sample_split(p.B, p.V, kBlock * DT::kPerVec, &p.S, &p.chunk);
+  const bool stats = (stages & EARS_STAGE_STATS) != 0;
+  const bool decide = (stages & EARS_STAGE_DECIDE) != 0;
+  const bool sample = (stages & EARS_STAGE_SAMPLE) != 0;
+  p.decide_fused = (decide && sample) ? 1 : 0;
+  if (stats) {
     hipLaunchKernelGGL((row_stats_kernel<DT, 4>), dim3((unsigned)(2 * p.R)), dim3(kBlock), 0, stream, p);
   }
-  if (stages & EARS_STAGE_DECIDE) {
-    hipLaunchKernelGGL(decide_kernel, dim3((unsigned)((p.B + kBlock - 1) / kBlock)), dim3(kBlock), 0,
-                       stream, p);
+  if (decide && !sample) {
+    hipLaunchKernelGGL(decide_kernel, dim3((unsigned)((p.B + kWavesPerBlock - 1) / kWavesPerBlock)),
+                       dim3(kBlock), 0, stream, p);
   }
-  if (stages & EARS_STAGE_SAMPLE) {
-    hipLaunchKernelGGL((sample_kernel<DT>), dim3((unsigned)p.B), dim3(kBlock), 0, stream, p);
+  if (sample) {
+    if (!stats) {  // the statistics kernel normally clears the arrival counters
+      hipLaunchKernelGGL(clear_arrivals_kernel, dim3((unsigned)((p.B + kBlock - 1) / kBlock)),
+                         dim3(kBlock), 0, stream, p.arrivals, p.B);
+    }
+    hipLaunchKernelGGL((sample_kernel<DT>), dim3((unsigned)p.S, (unsigned)p.B), dim3(kBlock), 0,
+                       stream, p);
   }
   return hipGetLastError() == hipSuccess ? EARS_OK : EARS_ERR_HIP;
 }
@@ -435,6 +206,11 @@ int ears_verify_ex(int dtype, const void* target_logits, const void* draft_logit
   p.Z = reinterpret_cast<double*>(ws + lay.off_Z);
   p.m = reinterpret_cast<float*>(ws + lay.off_m);
   p.lx = reinterpret_cast<float*>(ws + lay.off_lx);
+  p.arrivals = reinterpret_cast<uint32_t*>(ws + lay.off_arrivals);
+  p.records = reinterpret_cast<uint32_t*>(ws + lay.off_records);
+  p.S = 0;
+  p.chunk = 0;
+  p.decide_fused = 0;
   p.accept_len = out_accept_len;
   p.out_tokens = out_tokens;
   p.out_stats = out_stats;

@@ -1,0 +1,386 @@
+// Stage SAMPLE of the EARS verification step: the replacement token at the first rejected slot,
+// drawn from norm(max(0, p_t - p_d)), or the bonus token from the target row after the last draft
+// position when every draft token is accepted.  Both are Gumbel-max draws:
+//
+//     token = argmax_v  score(v),   score(v) = log w(v) + g(v),   g(v) = -log(-log u(v)),
+//     w(v) = max(0, p_t(v) - p_d(v))  (residual)   or   exp(l_t(v)/T)  (bonus),
+//
+// with u(v) from Philox keyed (seed, sequence, position, v); ties go to the lowest index.
+//
+// The winner is the one the fp64 definition gives; fp32 work only discards elements that provably
+// cannot win.  Three levels, each sound with respect to the next:
+//
+//  1. TEST, every element, no transcendental, target row only.  Since w(v) <= p_t(v) and
+//     -log u >= 1 - u, in base-2 logs
+//         score2(v) <= a(v) - log2(1 - u),   a(v) = (l_t(v) - m_t) * log2(e)/T - log2 Z_t
+//     (bonus: a(v) = l_t(v) * log2(e)/T), and log2(x) >= bits(x) * 2^-23 - 127 for a positive
+//     float x.  An element whose bound is below the running threshold theta (a lower bound of the
+//     best score seen so far) is dropped; the rest are queued.
+//  2. BOUNDS, queued elements, fp32 with explicit margins: s_lo <= score2 <= s_up.  theta rises
+//     to the largest s_lo; an element survives while s_up >= theta.
+//  3. EXACT, survivors only (a handful per row), fp64, by the workgroup that finishes last for
+//     the sequence: the definition above evaluated as written, argmax with lowest-index ties.
+//
+// Rows the bounds cannot separate (nearly identical target and draft rows, an empty residual,
+// a survivor list that overflows) fall back to an fp64 scan, so the result is always the
+// definition's.  The accept / first-reject scan runs in the prologue (one wave), so a whole
+// verification is two launches: row statistics, then this kernel.
+#pragma once
+
+#include "decide.h"
+#include "ears_device.h"
+
+namespace ears {
+
+constexpr int kSurvivorCap = kWave;            // survivors kept per wave while it filters
+constexpr float kExpMargin = 0x1p-12f;         // on a(v): covers fp32 rounding of (l-m)*c - log2 Z
+constexpr float kScoreMargin = 0x1p-12f;       // on the fp32 score: v_log_f32 / adds
+constexpr float kBonusMargin = 0x1p-10f;       // bonus scores carry l*c itself (|l|/T up to ~1e3)
+constexpr float kTestMargin = 0x1p-10f;        // slack of the level-1 test
+constexpr float kDegenerate = -100.0f;         // residual rows whose best lower bound is below
+                                               // 2^-100 are scanned in fp64 instead
+constexpr float kLog2Ln2Neg = 0.5287663729448977f;  // -log2(ln 2)
+// "no bound yet".  Finite, and still finite after scaling by 2^23, so that the level-1 bound of a
+// masked or out-of-range element (-inf) never reaches it.
+constexpr float kNoThreshold = -1.0e30f;
+
+enum { kModeResidual = 0, kModeBonus = 1, kModeTargetFallback = 2 };
+
+struct SampleCtx {
+  const void* trow;
+  const void* drow;
+  double mt, Zt, md, Zd, T;
+  uint64_t seed, seq;
+  uint32_t pos;
+  int V;
+};
+
+__device__ __forceinline__ uint32_t philox_pick(const Philox& blk, uint32_t v) {
+  return (v & 2u) ? ((v & 1u) ? blk.w[3] : blk.w[2]) : ((v & 1u) ? blk.w[1] : blk.w[0]);
+}
+
+// Level 3: the score exactly as defined, fp64.  -inf means "not a candidate".
+template <typename DT>
+__device__ double exact_score(const SampleCtx& c, int v, int mode) {
+  const double lt = (double)DT::load(c.trow, v);
+  double logw;
+  if (mode == kModeBonus) {
+    if (!(lt > -INFINITY)) return -INFINITY;
+    logw = lt / c.T;
+  } else {
+    const double pt = exp((lt - c.mt) / c.T) / c.Zt;
+    if (mode == kModeResidual) {
+      const double pd = exp(((double)DT::load(c.drow, v) - c.md) / c.T) / c.Zd;
+      const double q = pt - pd;
+      if (!(q > 0.0)) return -INFINITY;
+      logw = log(q);
+    } else {
+      if (!(pt > 0.0)) return -INFINITY;
+      logw = log(pt);
+    }
+  }
+  const uint32_t w = philox_pick(noise_block(c.seed, c.seq, c.pos, 1u, (uint32_t)v >> 2), (uint32_t)v);
+  const double u = (double)(w >> 9) * 0x1p-23 + 0x1p-24;
+  return logw - log(-log(u));
+}
+
+__device__ Best block_best(Best x) {
+  __shared__ double sh_s[kWavesPerBlock];
+  __shared__ int32_t sh_v[kWavesPerBlock];
+  x = wave_best(x);
+  const int lane = (int)threadIdx.x & (kWave - 1), wave = (int)threadIdx.x / kWave;
+  __syncthreads();
+  if (lane == 0) { sh_s[wave] = x.s; sh_v[wave] = x.v; }
+  __syncthreads();
+  Best r{sh_s[0], sh_v[0]};
+#pragma unroll
+  for (int w = 1; w < kWavesPerBlock; ++w)
+    if (better(sh_s[w], sh_v[w], r)) r = Best{sh_s[w], sh_v[w]};
+  return r;
+}
+
+template <typename DT>
+__device__ Best exact_scan(const SampleCtx& c, int v0, int v1, int mode, Best best) {
+  for (int v = v0 + (int)threadIdx.x; v < v1; v += kBlock) {
+    const double s = exact_score<DT>(c, v, mode);
+    if (s > -INFINITY && better(s, v, best)) best = Best{s, v};
+  }
+  return best;
+}
+
+__device__ __forceinline__ int lanes_below(unsigned long long mask) {
+  return (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32),
+                                        __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
+}
+
+template <typename DT>
+__global__ __launch_bounds__(kBlock) void sample_kernel(Problem p) {
+  constexpr int kPer = DT::kPerVec;
+  constexpr int kTile = kBlock * kPer;
+  constexpr int kQueueCap = kWave * kPer + kWave;
+  using storage = typename DT::storage;
+
+  __shared__ int sh_queue[kWavesPerBlock][kQueueCap];
+  __shared__ int sh_surv_v[kWavesPerBlock][kSurvivorCap];
+  __shared__ float sh_surv_s[kWavesPerBlock][kSurvivorCap];
+  __shared__ float sh_theta[kWavesPerBlock];
+  __shared__ int sh_n, sh_count, sh_overflow, sh_last;
+
+  const int tid = (int)threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
+  const int s = (int)blockIdx.x, b = (int)blockIdx.y;
+  const int V = p.V;
+
+  // ---- accept length of this sequence ---------------------------------------------------------
+  const int Kb = seq_len(p, b);
+  if (tid == 0) { sh_count = 0; sh_overflow = 0; }
+  if (p.decide_fused) {
+    if (wave == 0) {
+      const int nn = decide_sequence(p, b, lane, s == 0);
+      if (lane == 0) sh_n = nn;
+    }
+  } else if (tid == 0) {
+    const int nn = p.accept_len[b];
+    sh_n = nn < 0 ? 0 : (nn > Kb ? Kb : nn);
+  }
+  __syncthreads();
+  const int n = sh_n;
+
+  const int64_t r0 = seq_row_begin(p, b);
+  const bool residual = n < Kb;
+  const int64_t r = r0 + (residual ? n : Kb - 1);  // draft row of the rejected slot (if any)
+  const storage* trow = static_cast<const storage*>(p.target) + (r0 + b + n) * (int64_t)V;
+  const storage* drow = static_cast<const storage*>(p.draft) + r * (int64_t)V;
+  const float Tf = seq_temperature(p, b);
+  const uint64_t seed = p.seed, seq = seq_rng_id(p, b);
+  const uint32_t pos = (uint32_t)n;
+
+  // fp32 constants of levels 1 and 2
+  const float c = (float)(kLog2e / (double)Tf);
+  float mt = 0.0f, kt = 0.0f, md = 0.0f, kd = 0.0f;
+  if (residual) {
+    mt = p.m[2 * r];
+    md = p.m[2 * r + 1];
+    kt = -__builtin_amdgcn_logf((float)p.Z[2 * r]);
+    kd = -__builtin_amdgcn_logf((float)p.Z[2 * r + 1]);
+  }
+  const float cs = c * 0x1p23f;
+  const float ks = (kt + 127.0f + kTestMargin) * 0x1p23f;
+
+  float theta = kNoThreshold;  // wave-uniform: best proven lower bound of the maximum score (log2)
+  int qcount = 0;            // wave-uniform: queued candidates
+  int scount = 0;            // wave-uniform: survivors of this wave
+  bool overflow = false;
+
+  // Level 2 for up to 64 queued elements, one per lane.
+  auto evaluate = [&](int v, bool active, float& s_up, float& s_lo) {
+    s_up = -INFINITY;
+    s_lo = -INFINITY;
+    const int vv = active ? v : 0;
+    const float lt = DT::load(trow, vv);
+    const uint32_t w = philox_pick(noise_block(seed, seq, pos, 1u, (uint32_t)vv >> 2), (uint32_t)vv);
+    const float u = gumbel_uniform_from_word(w);
+    const float e2 = -__builtin_amdgcn_logf(u);                     // -log2 u > 0
+    const float g = kLog2Ln2Neg - __builtin_amdgcn_logf(e2);         // -log2(-ln u)
+    float up, lo;
+    if (residual) {
+      const float ld = DT::load(drow, vv);
+      const float at = fmaf(lt - mt, c, kt), ad = fmaf(ld - md, c, kd);
+      const float q_up = __builtin_amdgcn_exp2f(at + kExpMargin) - __builtin_amdgcn_exp2f(ad - kExpMargin);
+      const float q_lo = __builtin_amdgcn_exp2f(at - kExpMargin) - __builtin_amdgcn_exp2f(ad + kExpMargin);
+      up = q_up > 0.0f ? __builtin_amdgcn_logf(q_up) + g + kScoreMargin : -INFINITY;
+      lo = q_lo > 0.0f ? __builtin_amdgcn_logf(q_lo) + g - kScoreMargin : -INFINITY;
+    } else {
+      const float sc = fmaf(lt, c, g);
+      up = sc + kBonusMargin;
+      lo = sc - kBonusMargin;
+    }
+    if (active && up > -INFINITY) { s_up = up; s_lo = lo; }
+  };
+
+  auto compact_survivors = [&]() {
+    // drop survivors that the risen threshold has overtaken (one entry per lane)
+    const bool have = lane < scount;
+    const int v = have ? sh_surv_v[wave][lane] : 0;
+    const float su = have ? sh_surv_s[wave][lane] : -INFINITY;
+    const bool keep = have && su >= theta;
+    const unsigned long long km = __ballot(keep);
+    __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+    if (keep) {
+      const int slot = lanes_below(km);
+      sh_surv_v[wave][slot] = v;
+      sh_surv_s[wave][slot] = su;
+    }
+    scount = __popcll(km);
+    __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+  };
+
+  auto evaluate_batch = [&](int cnt) {
+    const bool active = lane < cnt;
+    __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+    const int v = active ? sh_queue[wave][qcount - cnt + lane] : 0;
+    qcount -= cnt;
+    float s_up, s_lo;
+    evaluate(v, active, s_up, s_lo);
+    theta = fmaxf(theta, wave_max(s_lo));
+    const bool surv = active && s_up > -INFINITY && s_up >= theta;
+    const unsigned long long sm = __ballot(surv);
+    const int add = __popcll(sm);
+    if (add == 0) return;
+    if (scount + add > kSurvivorCap) compact_survivors();
+    if (scount + add > kSurvivorCap) { overflow = true; return; }
+    if (surv) {
+      const int slot = scount + lanes_below(sm);
+      sh_surv_v[wave][slot] = v;
+      sh_surv_s[wave][slot] = s_up;
+    }
+    scount += add;
+    __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+  };
+
+  const int v_begin = s * p.chunk;
+  const int v_end = (V - v_begin) < p.chunk ? V : v_begin + p.chunk;
+  const bool vector_ok = (reinterpret_cast<uintptr_t>(trow) & 15u) == 0;
+
+  // warm start: a first threshold from 64 elements of this wave's part of the chunk
+  {
+    const int v = v_begin + wave * kWave + lane;
+    float s_up, s_lo;
+    evaluate(v, v < v_end, s_up, s_lo);
+    theta = fmaxf(theta, wave_max(s_lo));
+  }
+
+  for (int tile0 = v_begin; tile0 < v_end; tile0 += kTile) {
+    const int vbase = tile0 + tid * kPer;
+    float l[kPer];
+    if (vector_ok && vbase + kPer <= v_end) {
+      DT::unpack(*reinterpret_cast<const uint4*>(trow + vbase), l);
+    } else {
+#pragma unroll
+      for (int j = 0; j < kPer; ++j) l[j] = (vbase + j < v_end) ? DT::load(trow, vbase + j) : -INFINITY;
+    }
+    // level 1
+    const float Theta = theta * 0x1p23f;
+    uint32_t mask = 0;
+#pragma unroll
+    for (int g4 = 0; g4 < kPer / 4; ++g4) {
+      const Philox blk = noise_block(seed, seq, pos, 1u, (uint32_t)(vbase >> 2) + (uint32_t)g4);
+#pragma unroll
+      for (int j4 = 0; j4 < 4; ++j4) {
+        const int j = g4 * 4 + j4;
+        // 1 - u, exact; its bit pattern read as an integer is (log2(1-u) + 127) * 2^23 from below
+        const float one_minus_u = fmaf(-(float)(blk.w[j4] >> 9), 0x1p-23f, 1.0f - 0x1p-24f);
+        const float bound = fmaf(l[j] - mt, cs, ks) - (float)__float_as_int(one_minus_u);
+        if (bound >= Theta) mask |= 1u << j;
+      }
+    }
+    if (__ballot(mask != 0u) != 0ull) {
+#pragma unroll
+      for (int j = 0; j < kPer; ++j) {
+        const bool pj = (mask >> j) & 1u;
+        const unsigned long long bal = __ballot(pj);
+        if (bal != 0ull) {
+          if (pj) sh_queue[wave][qcount + lanes_below(bal)] = vbase + j;
+          qcount += __popcll(bal);
+        }
+      }
+      while (qcount >= kWave) evaluate_batch(kWave);
+    }
+  }
+  if (qcount > 0) evaluate_batch(qcount);
+  compact_survivors();
+
+  // ---- merge the four waves into this chunk's record -------------------------------------------
+  if (lane == 0) sh_theta[wave] = theta;
+  __syncthreads();
+  float theta_wg = sh_theta[0];
+#pragma unroll
+  for (int w = 1; w < kWavesPerBlock; ++w) theta_wg = fmaxf(theta_wg, sh_theta[w]);
+  uint32_t* rec = p.records + ((size_t)b * p.S + s) * kRecordWords;
+  {
+    const bool have = lane < scount;
+    const int v = have ? sh_surv_v[wave][lane] : 0;
+    const float su = have ? sh_surv_s[wave][lane] : -INFINITY;
+    const bool keep = have && su >= theta_wg;
+    const unsigned long long km = __ballot(keep);
+    int base = 0;
+    if (lane == 0 && km != 0ull) base = atomicAdd(&sh_count, __popcll(km));
+    base = __shfl(base, 0, 64);
+    if (keep) {
+      const int slot = base + lanes_below(km);
+      if (slot < kRecordCap) {
+        rec[2 + 2 * slot] = (uint32_t)v;
+        rec[3 + 2 * slot] = __float_as_uint(su);
+      }
+    }
+    if (overflow && lane == 0) sh_overflow = 1;
+  }
+  __syncthreads();
+  if (tid == 0) {
+    rec[0] = __float_as_uint(theta_wg);
+    rec[1] = (sh_overflow || sh_count > kRecordCap) ? (uint32_t)kRecordOverflow : (uint32_t)sh_count;
+  }
+
+  // ---- the workgroup that arrives last for this sequence picks the token ------------------------
+  __threadfence();
+  __syncthreads();
+  if (tid == 0) sh_last = (atomicAdd(&p.arrivals[b], 1u) == (uint32_t)(p.S - 1)) ? 1 : 0;
+  __syncthreads();
+  if (!sh_last) return;
+  __threadfence();
+
+  SampleCtx ctx;
+  ctx.trow = trow;
+  ctx.drow = drow;
+  ctx.mt = residual ? (double)p.m[2 * r] : 0.0;
+  ctx.Zt = residual ? p.Z[2 * r] : 1.0;
+  ctx.md = residual ? (double)p.m[2 * r + 1] : 0.0;
+  ctx.Zd = residual ? p.Z[2 * r + 1] : 1.0;
+  ctx.T = (double)Tf;
+  ctx.seed = seed;
+  ctx.seq = seq;
+  ctx.pos = pos;
+  ctx.V = V;
+  const int mode = residual ? kModeResidual : kModeBonus;
+  const volatile uint32_t* recs = p.records + (size_t)b * p.S * kRecordWords;
+
+  float theta_g = kNoThreshold;
+  for (int i = 0; i < p.S; ++i) theta_g = fmaxf(theta_g, __uint_as_float(recs[(size_t)i * kRecordWords]));
+  Best best{-INFINITY, -1};
+  const bool separable = theta_g > (residual ? kDegenerate : kNoThreshold);
+  if (separable) {
+    for (int idx = tid; idx < p.S * kRecordCap; idx += kBlock) {
+      const int i = idx / kRecordCap, j = idx - i * kRecordCap;
+      const volatile uint32_t* rc = recs + (size_t)i * kRecordWords;
+      const int cnt = (int)rc[1];
+      if (cnt != kRecordOverflow && j < cnt && __uint_as_float(rc[3 + 2 * j]) >= theta_g) {
+        const int v = (int)rc[2 + 2 * j];
+        const double sc = exact_score<DT>(ctx, v, mode);
+        if (sc > -INFINITY && better(sc, v, best)) best = Best{sc, v};
+      }
+    }
+    for (int i = 0; i < p.S; ++i) {
+      if ((int)recs[(size_t)i * kRecordWords + 1] == kRecordOverflow) {
+        const int c0 = i * p.chunk;
+        const int c1 = (V - c0) < p.chunk ? V : c0 + p.chunk;
+        best = exact_scan<DT>(ctx, c0, c1, mode, best);
+      }
+    }
+    best = block_best(best);
+  }
+  if (best.v < 0) {
+    // the bounds could not separate this row: evaluate the definition over the whole row
+    best = block_best(exact_scan<DT>(ctx, 0, V, mode, Best{-INFINITY, -1}));
+    if (best.v < 0 && residual)  // empty residual: draw from the target distribution itself
+      best = block_best(exact_scan<DT>(ctx, 0, V, kModeTargetFallback, Best{-INFINITY, -1}));
+  }
+  if (tid == 0) p.out_tokens[r0 + b + n] = best.v;
+}
+
+// Clears the per-sequence arrival counters when the sampling stage runs without the statistics
+// stage in the same call.
+__global__ __launch_bounds__(kBlock) void clear_arrivals_kernel(uint32_t* arrivals, int B) {
+  const int i = (int)(blockIdx.x * blockDim.x + threadIdx.x);
+  if (i < B) arrivals[i] = 0u;
+}
+
+}  // namespace ears
