@@ -7,48 +7,64 @@
 
 namespace ears {
 
-// One wave decides one sequence: lane i handles draft position i (positions beyond 64 in further
-// rounds); a ballot of the rejecting lanes gives the first rejection.  The B*K decision scalars
-// are evaluated in fp64 from the cached row statistics (row maximum m, Z = sum exp((l-m)/T) and
-// the draft token's logit), so the decision does not depend on fp32 rounding of R or the
-// threshold.  Returns the accept length n in every lane.  With write_outputs the wave also stores
-// the accept length, the accepted prefix and the -1 tail of out_tokens (slot n is left for the
-// sampling stage), and the optional per-position statistics / branch ids.
-__device__ __forceinline__ int decide_sequence(const Problem& p, int b, int lane, bool write_outputs) {
-  const int64_t r0 = seq_row_begin(p, b);
-  const int Kb = seq_len(p, b);
+// Decision for draft position i of sequence b (packed row r) from the row statistics: row maximum
+// m, Z = sum exp((l-m)/T) and the draft token's logit lx, for the target (t) and draft (d) rows.
+// Evaluated in fp64, so the outcome does not depend on fp32 rounding of R or the threshold.
+// Returns 0 reject, 1 accepted by R >= U, 2 accepted only through the tolerance.  Writes the
+// optional per-position statistics / branch id and raises the status bit for an invalid token.
+__device__ __forceinline__ int decide_position(const Problem& p, int b, int i, int64_t r, double mt,
+                                               double Zt, double lxt, double md, double Zd,
+                                               double lxd) {
   const double T = (double)seq_temperature(p, b);
   const double beta = (double)seq_beta(p, b);
-  const uint64_t seq = seq_rng_id(p, b);
+  const int32_t x = p.tokens[r];
+  const bool valid = x >= 0 && x < p.V;
+  const double Ptx = valid ? exp((lxt - mt) / T) / Zt : 0.0;
+  const double Pdx = valid ? exp((lxd - md) / T) / Zd : 0.0;
+  const double R = Ptx / fmax(Pdx, kEpsilon);                              // step 2, division guard
+  const double U = accept_uniform(p.seed, seq_rng_id(p, b), (uint32_t)i);  // step 3
+  const double unc = 1.0 - 1.0 / Zt;                      // 1 - max P_t; max P_t = 1/Z_t
+  const double tol = beta * unc;                          // step 4
+  const double thr = fmax(U - tol, 0.0);                  // threshold clamp
+  int decision;                                           // step 5
+  if (!valid) decision = 0;
+  else if (R >= U) decision = 1;
+  else if (R >= thr) decision = 2;
+  else decision = 0;
+  if (p.out_stats) {
+    double* d = p.out_stats + r * EARS_NSTATS;
+    d[0] = mt; d[1] = Zt; d[2] = Ptx; d[3] = md; d[4] = Zd; d[5] = Pdx;
+    d[6] = unc; d[7] = R; d[8] = U; d[9] = thr;
+  }
+  if (p.out_path) p.out_path[r] = decision;
+  if (!valid && p.status_word) atomicOr(p.status_word, 1u);
+  return decision;
+}
+
+// One wave finds the accept length of one sequence: lane i takes draft position i (positions
+// beyond 64 in further rounds) and a ballot of the rejecting lanes gives the first rejection.
+// The per-position decisions are read from p.decisions when from_memory is set (the statistics
+// kernel left them there), otherwise computed here from the cached row statistics and stored.
+// With write_outputs the wave also stores the accept length, the accepted prefix and the -1 tail
+// of out_tokens; slot n is left for the sampling stage.  Returns n in every lane.
+__device__ __forceinline__ int first_reject_scan(const Problem& p, int b, int lane, bool from_memory,
+                                                 bool write_outputs) {
+  const int64_t r0 = seq_row_begin(p, b);
+  const int Kb = seq_len(p, b);
   int n = Kb;
-  bool bad_token = false;
   for (int base = 0; base < Kb; base += kWave) {
-    if (n < Kb && !write_outputs) break;  // later positions cannot change n
+    if (n < Kb && from_memory) break;  // later positions cannot change n
     const int i = base + lane;
     int decision = 1;
     if (i < Kb) {
       const int64_t r = r0 + i;
-      const double mt = (double)p.m[2 * r], Zt = p.Z[2 * r], lxt = (double)p.lx[2 * r];
-      const double md = (double)p.m[2 * r + 1], Zd = p.Z[2 * r + 1], lxd = (double)p.lx[2 * r + 1];
-      const int32_t x = p.tokens[r];
-      const bool valid = x >= 0 && x < p.V;
-      const double Ptx = valid ? exp((lxt - mt) / T) / Zt : 0.0;
-      const double Pdx = valid ? exp((lxd - md) / T) / Zd : 0.0;
-      const double R = Ptx / fmax(Pdx, kEpsilon);               // step 2 with the division guard
-      const double U = accept_uniform(p.seed, seq, (uint32_t)i);  // step 3
-      const double unc = 1.0 - 1.0 / Zt;                        // 1 - max P_t; max P_t = 1/Z_t
-      const double tol = beta * unc;                            // step 4
-      const double thr = fmax(U - tol, 0.0);                    // threshold clamp
-      if (!valid) { decision = 0; bad_token = true; }           // step 5
-      else if (R >= U) decision = 1;
-      else if (R >= thr) decision = 2;
-      else decision = 0;
-      if (write_outputs && p.out_stats) {
-        double* d = p.out_stats + r * EARS_NSTATS;
-        d[0] = mt; d[1] = Zt; d[2] = Ptx; d[3] = md; d[4] = Zd; d[5] = Pdx;
-        d[6] = unc; d[7] = R; d[8] = U; d[9] = thr;
+      if (from_memory) {
+        decision = p.decisions[r];
+      } else {
+        decision = decide_position(p, b, i, r, (double)p.m[2 * r], p.Z[2 * r], (double)p.lx[2 * r],
+                                   (double)p.m[2 * r + 1], p.Z[2 * r + 1], (double)p.lx[2 * r + 1]);
+        p.decisions[r] = decision;
       }
-      if (write_outputs && p.out_path) p.out_path[r] = decision;
     }
     const unsigned long long rejecting = __ballot(decision == 0);
     if (rejecting != 0ull && n == Kb) n = base + (__ffsll((long long)rejecting) - 1);
@@ -58,7 +74,6 @@ __device__ __forceinline__ int decide_sequence(const Problem& p, int b, int lane
     int32_t* out = p.out_tokens + r0 + b;
     for (int i = lane; i <= Kb; i += kWave)
       if (i != n) out[i] = i < n ? p.tokens[r0 + i] : -1;
-    if (p.status_word && __ballot(bad_token) != 0ull && lane == 0) atomicOr(p.status_word, 1u);
   }
   return n;
 }
@@ -69,7 +84,7 @@ __global__ __launch_bounds__(kBlock) void decide_kernel(Problem p) {
   const int lane = (int)threadIdx.x & (kWave - 1);
   const int b = (int)blockIdx.x * kWavesPerBlock + (int)threadIdx.x / kWave;
   if (b >= p.B) return;
-  const int n = decide_sequence(p, b, lane, true);
+  const int n = first_reject_scan(p, b, lane, false, true);
   if (lane == 0) p.out_tokens[seq_row_begin(p, b) + b + n] = -1;
 }
 

@@ -42,12 +42,12 @@ struct Problem {
   double* Z;
   float* m;
   float* lx;
-  // sampling stage scratch: per-sequence arrival counters and per-chunk records
-  uint32_t* arrivals;   // [B]
+  int32_t* decisions;   // [R] per position: 0 reject, 1 primary accept, 2 accepted by tolerance
+  // sampling stage scratch: per-chunk records
   uint32_t* records;    // [B, S, kRecordWords]
   int S;                // chunks per row
   int chunk;            // vocabulary entries per chunk (a multiple of the tile size)
-  int decide_fused;     // the sampling kernel runs the decision scan itself
+  int decide_fused;     // statistics kernel decides each position; the filter kernel scans them
   // outputs
   int32_t* accept_len;
   int32_t* out_tokens;
@@ -83,6 +83,14 @@ __device__ __forceinline__ uint64_t seq_rng_id(const Problem& p, int b) {
 }
 
 // ---- logits --------------------------------------------------------------------------------
+// 16-byte load of data that is read once: the non-temporal hint keeps the stream from displacing
+// other lines in the caches, which on this part is worth more than a tenth of the read bandwidth.
+__device__ __forceinline__ uint4 load_stream(const uint4* ptr) {
+  typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+  const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(ptr));
+  return make_uint4(v.x, v.y, v.z, v.w);
+}
+
 struct F32 {
   using storage = float;
   static constexpr int kPerVec = 4;  // elements in one 16-byte load
@@ -120,7 +128,10 @@ struct BF16 {
 // Ten rounds; each multiplies counter words 0 and 2 by fixed odd constants and mixes the high
 // halves with the other words and the round key, which advances by two Weyl constants.
 struct Philox {
-  uint32_t w[4];
+  uint32_t w0, w1, w2, w3;
+  __device__ __forceinline__ uint32_t word(int i) const {  // i is a compile-time constant at every use
+    return i == 0 ? w0 : (i == 1 ? w1 : (i == 2 ? w2 : w3));
+  }
 };
 
 __device__ __forceinline__ Philox philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
@@ -138,9 +149,7 @@ __device__ __forceinline__ Philox philox4x32_10(uint32_t c0, uint32_t c1, uint32
     k0 += 0x9E3779B9u;
     k1 += 0xBB67AE85u;
   }
-  Philox r;
-  r.w[0] = c0; r.w[1] = c1; r.w[2] = c2; r.w[3] = c3;
-  return r;
+  return Philox{c0, c1, c2, c3};
 }
 
 // counter = (block, position, seq low 32, domain << 24 | seq bits 32..55); key = seed halves.
@@ -154,7 +163,7 @@ __device__ __forceinline__ Philox noise_block(uint64_t seed, uint64_t seq, uint3
 
 // U in [0,1) on a 2^-24 grid; u in (0,1) on a 2^-23 grid offset by 2^-24.  Both exact in fp32.
 __device__ __forceinline__ double accept_uniform(uint64_t seed, uint64_t seq, uint32_t pos) {
-  return (double)(noise_block(seed, seq, pos, 0u, 0u).w[0] >> 8) * 0x1p-24;
+  return (double)(noise_block(seed, seq, pos, 0u, 0u).w0 >> 8) * 0x1p-24;
 }
 __device__ __forceinline__ float gumbel_uniform_from_word(uint32_t w) {
   return (float)(w >> 9) * 0x1p-23f + 0x1p-24f;  // exact: 23-bit integer, then one more bit

@@ -4,8 +4,10 @@
 //                                       Section 3.3 item 1: max P_t cached, never re-scanned)
 //   stage DECIDE : decide_kernel      - ratio, uniform, tolerance, threshold, three-way decision,
 //                                       first-rejection scan (Section 3.2 steps 2-5, Section 3.1)
-//   stage SAMPLE : sample_kernel      - residual / bonus token by Gumbel-max at slot n; when DECIDE
-//                                       and SAMPLE run in one call the scan runs in its prologue
+//   stage SAMPLE : sample_kernel      - residual / bonus token by Gumbel-max at slot n: a filter that
+//                  select_kernel        leaves a few survivors per row, then the exact choice; when
+//                                       DECIDE and SAMPLE run in one call the scan runs in the
+//                                       filter's prologue
 //
 // The path is bound by HBM bandwidth (every needed row is read once, plus one re-read of the row
 // pair the sampler needs), so there is no matrix-core work here.
@@ -32,7 +34,7 @@ namespace ears {
 // Host side.
 // =================================================================================================
 struct WorkspaceLayout {
-  size_t off_Z, off_m, off_lx, off_arrivals, off_records, total;
+  size_t off_Z, off_m, off_lx, off_decisions, off_records, total;
   int S, chunk;  // how the sampling stage splits a row
 };
 
@@ -40,7 +42,9 @@ static size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 // The sampling stage touches only B rows, so each row is split into S chunks of whole tiles
 // (one tile = one 16-byte load per thread of a workgroup) until about kSampleTargetGroups
-// workgroups exist: enough waves per CU to overlap the row reads with the Philox arithmetic.
+// workgroups exist.  The filter is bound by vector-ALU issue (Philox), so more, shorter
+// workgroups only add their fixed prologue cost: 512-2048 groups measure within 10% of each
+// other on 256 CUs, 1024 best.
 constexpr int kSampleTargetGroups = 1024;
 
 static void sample_split(int B, int V, int elems_per_tile, int* S, int* chunk) {
@@ -64,7 +68,7 @@ static bool workspace_layout(int64_t R, int B, int V, WorkspaceLayout* w) {
   w->off_Z = o;        o = align_up(o + (size_t)(2 * R) * sizeof(double), 256);
   w->off_m = o;        o = align_up(o + (size_t)(2 * R) * sizeof(float), 256);
   w->off_lx = o;       o = align_up(o + (size_t)(2 * R) * sizeof(float), 256);
-  w->off_arrivals = o; o = align_up(o + (size_t)B * sizeof(uint32_t), 256);
+  w->off_decisions = o; o = align_up(o + (size_t)R * sizeof(int32_t), 256);
   w->off_records = o;  o = align_up(o + (size_t)B * S4 * kRecordWords * sizeof(uint32_t), 256);
   w->total = o;
   return true;
@@ -105,21 +109,25 @@ static int launch(Problem p, int stages, hipStream_t stream) {
   const bool stats = (stages & EARS_STAGE_STATS) != 0;
   const bool decide = (stages & EARS_STAGE_DECIDE) != 0;
   const bool sample = (stages & EARS_STAGE_SAMPLE) != 0;
-  p.decide_fused = (decide && sample) ? 1 : 0;
+  // All three stages in one call: the statistics kernel decides each position as it finishes it
+  // and the filter kernel's prologue scans the decisions for the first rejection.  Otherwise a
+  // small kernel decides and scans from the cached statistics.
+  const bool fused = stats && decide && sample;
+  p.decide_fused = fused ? 1 : 0;
   if (stats) {
-    hipLaunchKernelGGL((row_stats_kernel<DT, 4>), dim3((unsigned)(2 * p.R)), dim3(kBlock), 0, stream, p);
+    if (fused)
+      hipLaunchKernelGGL((row_stats_kernel<DT, 4, true>), dim3((unsigned)p.R), dim3(kBlock), 0, stream, p);
+    else
+      hipLaunchKernelGGL((row_stats_kernel<DT, 4, false>), dim3((unsigned)p.R), dim3(kBlock), 0, stream, p);
   }
-  if (decide && !sample) {
+  if (decide && !fused) {
     hipLaunchKernelGGL(decide_kernel, dim3((unsigned)((p.B + kWavesPerBlock - 1) / kWavesPerBlock)),
                        dim3(kBlock), 0, stream, p);
   }
   if (sample) {
-    if (!stats) {  // the statistics kernel normally clears the arrival counters
-      hipLaunchKernelGGL(clear_arrivals_kernel, dim3((unsigned)((p.B + kBlock - 1) / kBlock)),
-                         dim3(kBlock), 0, stream, p.arrivals, p.B);
-    }
     hipLaunchKernelGGL((sample_kernel<DT>), dim3((unsigned)p.S, (unsigned)p.B), dim3(kBlock), 0,
                        stream, p);
+    hipLaunchKernelGGL((select_kernel<DT>), dim3((unsigned)p.B), dim3(kBlock), 0, stream, p);
   }
   return hipGetLastError() == hipSuccess ? EARS_OK : EARS_ERR_HIP;
 }
@@ -206,7 +214,7 @@ int ears_verify_ex(int dtype, const void* target_logits, const void* draft_logit
   p.Z = reinterpret_cast<double*>(ws + lay.off_Z);
   p.m = reinterpret_cast<float*>(ws + lay.off_m);
   p.lx = reinterpret_cast<float*>(ws + lay.off_lx);
-  p.arrivals = reinterpret_cast<uint32_t*>(ws + lay.off_arrivals);
+  p.decisions = reinterpret_cast<int32_t*>(ws + lay.off_decisions);
   p.records = reinterpret_cast<uint32_t*>(ws + lay.off_records);
   p.S = 0;
   p.chunk = 0;

@@ -18,13 +18,13 @@
 //     best score seen so far) is dropped; the rest are queued.
 //  2. BOUNDS, queued elements, fp32 with explicit margins: s_lo <= score2 <= s_up.  theta rises
 //     to the largest s_lo; an element survives while s_up >= theta.
-//  3. EXACT, survivors only (a handful per row), fp64, by the workgroup that finishes last for
-//     the sequence: the definition above evaluated as written, argmax with lowest-index ties.
+//  3. EXACT (select_kernel, one workgroup per sequence): a lone survivor wins as it stands; several
+//     are scored in fp64 by the definition above as written, argmax with lowest-index ties.
 //
 // Rows the bounds cannot separate (nearly identical target and draft rows, an empty residual,
 // a survivor list that overflows) fall back to an fp64 scan, so the result is always the
-// definition's.  The accept / first-reject scan runs in the prologue (one wave), so a whole
-// verification is two launches: row statistics, then this kernel.
+// definition's.  The accept / first-reject scan runs in the filter kernel's prologue (one wave),
+// so a whole verification is three back-to-back launches: row statistics, filter, select.
 #pragma once
 
 #include "decide.h"
@@ -55,8 +55,12 @@ struct SampleCtx {
   int V;
 };
 
-__device__ __forceinline__ uint32_t philox_pick(const Philox& blk, uint32_t v) {
-  return (v & 2u) ? ((v & 1u) ? blk.w[3] : blk.w[2]) : ((v & 1u) ? blk.w[1] : blk.w[0]);
+// word v & 3 of a block, by value selects (no indexed access to the block)
+__device__ __forceinline__ uint32_t philox_pick(const Philox blk, uint32_t v) {
+  const uint32_t w0 = blk.w0, w1 = blk.w1, w2 = blk.w2, w3 = blk.w3;
+  const uint32_t lo = (v & 1u) ? w1 : w0;
+  const uint32_t hi = (v & 1u) ? w3 : w2;
+  return (v & 2u) ? hi : lo;
 }
 
 // Level 3: the score exactly as defined, fp64.  -inf means "not a candidate".
@@ -117,14 +121,14 @@ template <typename DT>
 __global__ __launch_bounds__(kBlock) void sample_kernel(Problem p) {
   constexpr int kPer = DT::kPerVec;
   constexpr int kTile = kBlock * kPer;
-  constexpr int kQueueCap = kWave * kPer + kWave;
+  constexpr int kQueueCap = 2 * kWave;  // drained as soon as it holds a full batch
   using storage = typename DT::storage;
 
   __shared__ int sh_queue[kWavesPerBlock][kQueueCap];
   __shared__ int sh_surv_v[kWavesPerBlock][kSurvivorCap];
   __shared__ float sh_surv_s[kWavesPerBlock][kSurvivorCap];
   __shared__ float sh_theta[kWavesPerBlock];
-  __shared__ int sh_n, sh_count, sh_overflow, sh_last;
+  __shared__ int sh_n, sh_count, sh_overflow;
 
   const int tid = (int)threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
   const int s = (int)blockIdx.x, b = (int)blockIdx.y;
@@ -134,8 +138,9 @@ __global__ __launch_bounds__(kBlock) void sample_kernel(Problem p) {
   const int Kb = seq_len(p, b);
   if (tid == 0) { sh_count = 0; sh_overflow = 0; }
   if (p.decide_fused) {
+    // the statistics kernel left one decision per position; scan them for the first rejection
     if (wave == 0) {
-      const int nn = decide_sequence(p, b, lane, s == 0);
+      const int nn = first_reject_scan(p, b, lane, true, s == 0);
       if (lane == 0) sh_n = nn;
     }
   } else if (tid == 0) {
@@ -241,7 +246,29 @@ __global__ __launch_bounds__(kBlock) void sample_kernel(Problem p) {
   const int v_end = (V - v_begin) < p.chunk ? V : v_begin + p.chunk;
   const bool vector_ok = (reinterpret_cast<uintptr_t>(trow) & 15u) == 0;
 
-  // warm start: a first threshold from 64 elements of this wave's part of the chunk
+  // One 16-byte load per lane and tile; rows that are not 16-byte aligned (or the ragged last
+  // vector) are assembled from element loads into the same packed form, padded with -inf.
+  auto load_raw = [&](int vb) -> uint4 {
+    if (vb >= v_end) return DT::neg_inf_vec();
+    if (vector_ok && vb + kPer <= v_end) return load_stream(reinterpret_cast<const uint4*>(trow + vb));
+    uint32_t wds[4];
+#pragma unroll
+    for (int d = 0; d < 4; ++d) {
+      if (sizeof(storage) == 2) {
+        const uint32_t lo = (vb + 2 * d < v_end) ? (uint32_t)reinterpret_cast<const uint16_t*>(trow)[vb + 2 * d] : 0xFF80u;
+        const uint32_t hi = (vb + 2 * d + 1 < v_end) ? (uint32_t)reinterpret_cast<const uint16_t*>(trow)[vb + 2 * d + 1] : 0xFF80u;
+        wds[d] = lo | (hi << 16);
+      } else {
+        wds[d] = (vb + d < v_end) ? reinterpret_cast<const uint32_t*>(trow)[vb + d] : 0xFF800000u;
+      }
+    }
+    return make_uint4(wds[0], wds[1], wds[2], wds[3]);
+  };
+
+  uint4 raw = load_raw(v_begin + tid * kPer);
+
+  // warm start: a first threshold from 64 elements of this wave's part of the chunk (their loads
+  // travel together with the first tile's)
   {
     const int v = v_begin + wave * kWave + lane;
     float s_up, s_lo;
@@ -251,13 +278,10 @@ __global__ __launch_bounds__(kBlock) void sample_kernel(Problem p) {
 
   for (int tile0 = v_begin; tile0 < v_end; tile0 += kTile) {
     const int vbase = tile0 + tid * kPer;
+    const uint4 raw_next = load_raw(vbase + kTile);  // in flight while this tile is tested
     float l[kPer];
-    if (vector_ok && vbase + kPer <= v_end) {
-      DT::unpack(*reinterpret_cast<const uint4*>(trow + vbase), l);
-    } else {
-#pragma unroll
-      for (int j = 0; j < kPer; ++j) l[j] = (vbase + j < v_end) ? DT::load(trow, vbase + j) : -INFINITY;
-    }
+    DT::unpack(raw, l);
+    raw = raw_next;
     // level 1
     const float Theta = theta * 0x1p23f;
     uint32_t mask = 0;
@@ -268,7 +292,7 @@ __global__ __launch_bounds__(kBlock) void sample_kernel(Problem p) {
       for (int j4 = 0; j4 < 4; ++j4) {
         const int j = g4 * 4 + j4;
         // 1 - u, exact; its bit pattern read as an integer is (log2(1-u) + 127) * 2^23 from below
-        const float one_minus_u = fmaf(-(float)(blk.w[j4] >> 9), 0x1p-23f, 1.0f - 0x1p-24f);
+        const float one_minus_u = fmaf(-(float)(blk.word(j4) >> 9), 0x1p-23f, 1.0f - 0x1p-24f);
         const float bound = fmaf(l[j] - mt, cs, ks) - (float)__float_as_int(one_minus_u);
         if (bound >= Theta) mask |= 1u << j;
       }
@@ -281,9 +305,9 @@ __global__ __launch_bounds__(kBlock) void sample_kernel(Problem p) {
         if (bal != 0ull) {
           if (pj) sh_queue[wave][qcount + lanes_below(bal)] = vbase + j;
           qcount += __popcll(bal);
+          if (qcount >= kWave) evaluate_batch(kWave);
         }
       }
-      while (qcount >= kWave) evaluate_batch(kWave);
     }
   }
   if (qcount > 0) evaluate_batch(qcount);
@@ -319,40 +343,102 @@ __global__ __launch_bounds__(kBlock) void sample_kernel(Problem p) {
     rec[0] = __float_as_uint(theta_wg);
     rec[1] = (sh_overflow || sh_count > kRecordCap) ? (uint32_t)kRecordOverflow : (uint32_t)sh_count;
   }
+}
 
-  // ---- the workgroup that arrives last for this sequence picks the token ------------------------
-  __threadfence();
-  __syncthreads();
-  if (tid == 0) sh_last = (atomicAdd(&p.arrivals[b], 1u) == (uint32_t)(p.S - 1)) ? 1 : 0;
-  __syncthreads();
-  if (!sh_last) return;
-  __threadfence();
+// Level 3.  One workgroup per sequence reads the chunk records of the filter kernel.  A single
+// survivor is the winner as it stands; several are scored in fp64 by the definition; rows the
+// bounds could not separate are scanned in fp64.  In the common case everything this kernel needs
+// (accept length, chunk headers, survivor entries) is requested in one round of loads.
+template <typename DT>
+__global__ __launch_bounds__(kBlock) void select_kernel(Problem p) {
+  using storage = typename DT::storage;
+  __shared__ float sh_theta[kWavesPerBlock];
+  __shared__ int sh_any_overflow, sh_total, sh_only;
+  const int tid = (int)threadIdx.x;
+  const int b = (int)blockIdx.x;
+  const int V = p.V;
+  const uint32_t* recs = p.records + (size_t)b * p.S * kRecordWords;
+  const int total = p.S * kRecordCap;
 
+  // ---- one round of loads ---------------------------------------------------------------------
+  const int n_raw = p.accept_len[b];
+  const int64_t r0 = seq_row_begin(p, b);
+  const int Kb = seq_len(p, b);
+  float th = kNoThreshold;
+  bool ovf = false;
+  for (int i = tid; i < p.S; i += kBlock) {
+    th = fmaxf(th, __uint_as_float(recs[(size_t)i * kRecordWords]));
+    ovf = ovf || (int)recs[(size_t)i * kRecordWords + 1] == kRecordOverflow;
+  }
+  // this thread's survivor entry (further entries, for rows split into many chunks, come later)
+  int e_cnt = 0, e_j = 0, e_v = -1;
+  float e_s = -INFINITY;
+  if (tid < total) {
+    const int i = tid / kRecordCap;
+    e_j = tid - i * kRecordCap;
+    const uint32_t* rc = recs + (size_t)i * kRecordWords;
+    e_cnt = (int)rc[1];
+    e_v = (int)rc[2 + 2 * e_j];
+    e_s = __uint_as_float(rc[3 + 2 * e_j]);
+  }
+  if (tid == 0) { sh_any_overflow = 0; sh_total = 0; sh_only = -1; }
+
+  // ---- best lower bound over the chunks of this row ----------------------------------------------
+  th = wave_max(th);
+  __syncthreads();
+  if ((tid & (kWave - 1)) == 0) sh_theta[tid / kWave] = th;
+  if (ovf) sh_any_overflow = 1;
+  __syncthreads();
+  float theta_g = sh_theta[0];
+#pragma unroll
+  for (int w = 1; w < kWavesPerBlock; ++w) theta_g = fmaxf(theta_g, sh_theta[w]);
+  const bool any_overflow = sh_any_overflow != 0;
+
+  const int n = n_raw < 0 ? 0 : (n_raw > Kb ? Kb : n_raw);
+  const bool residual = n < Kb;
+  const bool separable = theta_g > (residual ? kDegenerate : kNoThreshold);
+
+  // ---- survivors of the whole row: entries whose upper bound reaches the best lower bound --------
+  auto is_survivor = [&](int cnt, int j, float su) {
+    return cnt != kRecordOverflow && j < cnt && su >= theta_g;
+  };
+  int mine = 0, my_v = -1;
+  if (separable) {
+    if (is_survivor(e_cnt, e_j, e_s)) { mine = 1; my_v = e_v; }
+    for (int idx = tid + kBlock; idx < total; idx += kBlock) {
+      const int i = idx / kRecordCap, j = idx - i * kRecordCap;
+      const uint32_t* rc = recs + (size_t)i * kRecordWords;
+      if (is_survivor((int)rc[1], j, __uint_as_float(rc[3 + 2 * j]))) { ++mine; my_v = (int)rc[2 + 2 * j]; }
+    }
+    if (mine > 0) { atomicAdd(&sh_total, mine); sh_only = my_v; }
+  }
+  __syncthreads();
+  if (separable && !any_overflow && sh_total == 1) {
+    if (tid == 0) p.out_tokens[r0 + b + n] = sh_only;  // nothing to compare it with
+    return;
+  }
+
+  // ---- several survivors, or a row the bounds could not separate: fp64 ---------------------------
+  const int64_t r = r0 + (residual ? n : Kb - 1);
   SampleCtx ctx;
-  ctx.trow = trow;
-  ctx.drow = drow;
+  ctx.trow = static_cast<const storage*>(p.target) + (r0 + b + n) * (int64_t)V;
+  ctx.drow = static_cast<const storage*>(p.draft) + r * (int64_t)V;
   ctx.mt = residual ? (double)p.m[2 * r] : 0.0;
   ctx.Zt = residual ? p.Z[2 * r] : 1.0;
   ctx.md = residual ? (double)p.m[2 * r + 1] : 0.0;
   ctx.Zd = residual ? p.Z[2 * r + 1] : 1.0;
-  ctx.T = (double)Tf;
-  ctx.seed = seed;
-  ctx.seq = seq;
-  ctx.pos = pos;
+  ctx.T = (double)seq_temperature(p, b);
+  ctx.seed = p.seed;
+  ctx.seq = seq_rng_id(p, b);
+  ctx.pos = (uint32_t)n;
   ctx.V = V;
   const int mode = residual ? kModeResidual : kModeBonus;
-  const volatile uint32_t* recs = p.records + (size_t)b * p.S * kRecordWords;
-
-  float theta_g = kNoThreshold;
-  for (int i = 0; i < p.S; ++i) theta_g = fmaxf(theta_g, __uint_as_float(recs[(size_t)i * kRecordWords]));
   Best best{-INFINITY, -1};
-  const bool separable = theta_g > (residual ? kDegenerate : kNoThreshold);
   if (separable) {
-    for (int idx = tid; idx < p.S * kRecordCap; idx += kBlock) {
+    for (int idx = tid; idx < total; idx += kBlock) {
       const int i = idx / kRecordCap, j = idx - i * kRecordCap;
-      const volatile uint32_t* rc = recs + (size_t)i * kRecordWords;
-      const int cnt = (int)rc[1];
-      if (cnt != kRecordOverflow && j < cnt && __uint_as_float(rc[3 + 2 * j]) >= theta_g) {
+      const uint32_t* rc = recs + (size_t)i * kRecordWords;
+      if (is_survivor((int)rc[1], j, __uint_as_float(rc[3 + 2 * j]))) {
         const int v = (int)rc[2 + 2 * j];
         const double sc = exact_score<DT>(ctx, v, mode);
         if (sc > -INFINITY && better(sc, v, best)) best = Best{sc, v};
@@ -374,13 +460,6 @@ __global__ __launch_bounds__(kBlock) void sample_kernel(Problem p) {
       best = block_best(exact_scan<DT>(ctx, 0, V, kModeTargetFallback, Best{-INFINITY, -1}));
   }
   if (tid == 0) p.out_tokens[r0 + b + n] = best.v;
-}
-
-// Clears the per-sequence arrival counters when the sampling stage runs without the statistics
-// stage in the same call.
-__global__ __launch_bounds__(kBlock) void clear_arrivals_kernel(uint32_t* arrivals, int B) {
-  const int i = (int)(blockIdx.x * blockDim.x + threadIdx.x);
-  if (i < B) arrivals[i] = 0u;
 }
 
 }  // namespace ears
