@@ -49,9 +49,14 @@ double ears_oracle_accept_uniform(uint64_t seed, uint64_t seq, uint32_t pos) {
   return (double)(w >> 8) * 0x1p-24;
 }
 
+/* Uniform of vocabulary entry v: 8 leading bits from one byte of a "coarse" block shared by 16
+ * consecutive entries, 32 further bits from a "fine" word; a half-step offset keeps it off 0 and
+ * 1.  u = (h + (f + 1/2) * 2^-32) * 2^-8, exact in a double. */
 double ears_oracle_gumbel_uniform(uint64_t seed, uint64_t seq, uint32_t pos, uint32_t v) {
-  uint32_t w = ears_oracle_philox_word(seed, seq, pos, 1u, v >> 2, v & 3u);
-  return (double)(w >> 9) * 0x1p-23 + 0x1p-24;
+  uint32_t cw = ears_oracle_philox_word(seed, seq, pos, 1u, v >> 4, (v >> 2) & 3u);
+  uint32_t h = (cw >> (8u * (v & 3u))) & 0xffu;
+  uint32_t f = ears_oracle_philox_word(seed, seq, pos, 2u, v >> 2, v & 3u);
+  return ((double)h + ((double)f + 0.5) * 0x1p-32) * 0x1p-8;
 }
 
 double ears_oracle_gumbel(uint64_t seed, uint64_t seq, uint32_t pos, uint32_t v) {

@@ -57,14 +57,17 @@ void ears_oracle_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uin
  *   key     = (seed & 0xffffffff, seed >> 32)
  *   counter = (blk, pos, seq & 0xffffffff, (domain << 24) | ((seq >> 32) & 0xffffff))
  *   domain 0: acceptance uniform of (seq, pos): blk = 0, word 0
- *   domain 1: Gumbel noise of (seq, pos, v):    blk = v >> 2, word v & 3
+ *   domain 1: coarse Gumbel bits of (seq, pos, v): blk = v >> 4, word (v >> 2) & 3,
+ *             byte v & 3 of that word (byte k = bits 8k .. 8k+7)
+ *   domain 2: fine Gumbel bits of (seq, pos, v):   blk = v >> 2, word v & 3
  */
 uint32_t ears_oracle_philox_word(uint64_t seed, uint64_t seq, uint32_t pos, uint32_t domain,
                                  uint32_t blk, uint32_t word);
 
 /* U = (w >> 8) * 2^-24, in [0, 1), exactly representable in fp32. */
 double ears_oracle_accept_uniform(uint64_t seed, uint64_t seq, uint32_t pos);
-/* u = (w >> 9) * 2^-23 + 2^-24, in (0, 1), exactly representable in fp32. */
+/* u = (h + (f + 1/2) * 2^-32) * 2^-8 in (0, 1): h the coarse byte, f the fine word; exact in fp64.
+ * (The split lets a GPU discard almost every entry from the coarse byte alone.) */
 double ears_oracle_gumbel_uniform(uint64_t seed, uint64_t seq, uint32_t pos, uint32_t v);
 /* g = -log(-log(u)), standard Gumbel noise. */
 double ears_oracle_gumbel(uint64_t seed, uint64_t seq, uint32_t pos, uint32_t v);

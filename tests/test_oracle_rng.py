@@ -44,36 +44,44 @@ def test_word_layout(oracle):
     blk = oracle.philox4x32_10([0, pos, seq & 0xFFFFFFFF, (0 << 24) | (seq >> 32)], key)
     assert philox_word(seed, seq, pos, 0, 0, 0) == blk[0]
     assert oracle.accept_uniform(seed, seq, pos) == (blk[0] >> 8) * 2.0 ** -24
-    # Gumbel noise: domain 1, one block per four vocabulary indices
-    for v in (0, 1, 2, 3, 4, 1023, 128255):
-        blk = oracle.philox4x32_10([v >> 2, pos, seq & 0xFFFFFFFF, (1 << 24) | (seq >> 32)], key)
-        w = blk[v & 3]
-        u = (w >> 9) * 2.0 ** -23 + 2.0 ** -24
+    # Gumbel noise: 8 coarse bits (domain 1, one block per sixteen vocabulary indices, one byte
+    # each) and 32 fine bits (domain 2, one block per four indices, one word each)
+    for v in (0, 1, 2, 3, 4, 5, 15, 16, 17, 1023, 128255):
+        coarse = oracle.philox4x32_10([v >> 4, pos, seq & 0xFFFFFFFF, (1 << 24) | (seq >> 32)], key)
+        fine = oracle.philox4x32_10([v >> 2, pos, seq & 0xFFFFFFFF, (2 << 24) | (seq >> 32)], key)
+        h = (coarse[(v >> 2) & 3] >> (8 * (v & 3))) & 0xFF
+        f = fine[v & 3]
+        u = (h + (f + 0.5) / 2.0 ** 32) / 256.0
         assert oracle.gumbel_uniform(seed, seq, pos, v) == u
         assert oracle.gumbel(seed, seq, pos, v) == pytest.approx(-math.log(-math.log(u)), rel=1e-15)
 
 
-def test_uniform_ranges_and_fp32_exactness(oracle):
+def test_uniform_ranges_and_exactness(oracle):
     us = np.array([oracle.accept_uniform(11, s, p) for s in range(300) for p in range(8)])
     gs = np.array([oracle.gumbel_uniform(11, s, 0, v) for s in range(30) for v in range(80)])
     assert us.min() >= 0.0 and us.max() < 1.0
     assert gs.min() > 0.0 and gs.max() < 1.0
-    # both mappings land on values an fp32 holds exactly
+    # the acceptance uniform lands on values an fp32 holds exactly; the Gumbel uniform on odd
+    # multiples of 2^-41 (exact in fp64)
     assert np.all(us.astype(np.float32).astype(np.float64) == us)
-    assert np.all(gs.astype(np.float32).astype(np.float64) == gs)
-    # and look uniform (Kolmogorov-Smirnov)
+    k = gs * 2.0 ** 41
+    assert np.all(k == np.floor(k)) and np.all(k % 2 == 1)
+    # and both look uniform (Kolmogorov-Smirnov)
     from scipy import stats
     assert stats.kstest(us, "uniform").pvalue > 1e-3
     assert stats.kstest(gs, "uniform").pvalue > 1e-3
+    # the coarse byte alone is uniform over its 256 values
+    hs = np.floor(np.array([oracle.gumbel_uniform(3, 1, 2, v) for v in range(20000)]) * 256).astype(int)
+    assert stats.chisquare(np.bincount(hs, minlength=256)).pvalue > 1e-3
 
 
 def test_gumbel_extremes():
     # the smallest and largest u the mapping can produce bound the noise
-    u_min = 0 * 2.0 ** -23 + 2.0 ** -24
-    u_max = ((0xFFFFFFFF >> 9)) * 2.0 ** -23 + 2.0 ** -24
-    assert u_max == 1.0 - 2.0 ** -24
-    assert -math.log(-math.log(u_min)) == pytest.approx(-2.8115, abs=1e-4)
-    assert -math.log(-math.log(u_max)) == pytest.approx(16.6355, abs=1e-4)
+    u_min = (0 + (0 + 0.5) / 2.0 ** 32) / 256.0
+    u_max = (255 + (2 ** 32 - 1 + 0.5) / 2.0 ** 32) / 256.0
+    assert u_min == 2.0 ** -41 and u_max == 1.0 - 2.0 ** -41
+    assert -math.log(-math.log(u_min)) == pytest.approx(-math.log(41 * math.log(2.0)), abs=1e-12)
+    assert -math.log(-math.log(u_max)) == pytest.approx(41 * math.log(2.0), abs=1e-9)
 
 
 def test_gumbel_law(oracle):
