@@ -19,6 +19,9 @@ constexpr double kEpsilon = 1e-10;      // division guard of the paper's Section
 constexpr int kRecordCap = 48;
 constexpr int kRecordWords = 2 + 2 * kRecordCap + 2;
 constexpr int kRecordOverflow = -1;
+// The filter hands each lane 16 consecutive vocabulary entries per tile (one coarse Philox block).
+constexpr int kSampleLaneElems = 16;
+constexpr int kSampleTileElems = kBlock * kSampleLaneElems;
 
 // Everything a kernel needs to locate its rows.  Rectangular batches have row_offsets == nullptr:
 // sequence b then owns draft rows b*K .. b*K+K-1.  In both layouts draft row r of sequence b
@@ -153,8 +156,13 @@ __device__ __forceinline__ Philox philox4x32_10(uint32_t c0, uint32_t c1, uint32
 }
 
 // counter = (block, position, seq low 32, domain << 24 | seq bits 32..55); key = seed halves.
-// domain 0: acceptance uniform (block 0, word 0); domain 1: Gumbel noise, block = v >> 2,
-// word = v & 3.
+// domain 0: acceptance uniform (block 0, word 0);
+// domain 1: coarse Gumbel bits, block = v >> 4, one byte per vocabulary entry (word (v >> 2) & 3,
+//           byte v & 3, byte k = bits 8k..8k+7);
+// domain 2: fine Gumbel bits, block = v >> 2, word = v & 3.
+// The Gumbel uniform of entry v is u = (h + (f + 1/2) * 2^-32) * 2^-8, h the coarse byte and f the
+// fine word: the byte alone bounds -log(-log u) from above, which is all the filter needs for
+// almost every entry.
 __device__ __forceinline__ Philox noise_block(uint64_t seed, uint64_t seq, uint32_t pos,
                                               uint32_t domain, uint32_t blk) {
   return philox4x32_10(blk, pos, (uint32_t)seq, (domain << 24) | ((uint32_t)(seq >> 32) & 0xFFFFFFu),
@@ -165,9 +173,7 @@ __device__ __forceinline__ Philox noise_block(uint64_t seed, uint64_t seq, uint3
 __device__ __forceinline__ double accept_uniform(uint64_t seed, uint64_t seq, uint32_t pos) {
   return (double)(noise_block(seed, seq, pos, 0u, 0u).w0 >> 8) * 0x1p-24;
 }
-__device__ __forceinline__ float gumbel_uniform_from_word(uint32_t w) {
-  return (float)(w >> 9) * 0x1p-23f + 0x1p-24f;  // exact: 23-bit integer, then one more bit
-}
+constexpr uint32_t kDomainAccept = 0u, kDomainCoarse = 1u, kDomainFine = 2u;
 
 // ---- wave64 all-reduce through DPP / swizzle / permlane ---------------------------------------
 // After the call every lane of the wave holds the reduction.  Steps: xor 1 and xor 2 inside a

@@ -41,7 +41,7 @@ struct WorkspaceLayout {
 static size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 // The sampling stage touches only B rows, so each row is split into S chunks of whole tiles
-// (one tile = one 16-byte load per thread of a workgroup) until about kSampleTargetGroups
+// (one tile = 16 vocabulary entries per thread of a workgroup) until about kSampleTargetGroups
 // workgroups exist.  The filter is bound by vector-ALU issue (Philox), so more, shorter
 // workgroups only add their fixed prologue cost: 512-2048 groups measure within 10% of each
 // other on 256 CUs, 1024 best.
@@ -59,11 +59,8 @@ static void sample_split(int B, int V, int elems_per_tile, int* S, int* chunk) {
 
 static bool workspace_layout(int64_t R, int B, int V, WorkspaceLayout* w) {
   if (R < 1 || B < 1 || V < 1 || R < B || R > (int64_t)0x3FFFFFFF) return false;
-  // records are sized for whichever of the two tilings (4 or 8 elements per 16 bytes) splits finer
-  int S4, S8, chunk;
-  sample_split(B, V, kBlock * 4, &S4, &chunk);
-  sample_split(B, V, kBlock * 8, &S8, &chunk);
-  if (S8 > S4) S4 = S8;
+  int S4, chunk;
+  sample_split(B, V, kSampleTileElems, &S4, &chunk);
   size_t o = 0;
   w->off_Z = o;        o = align_up(o + (size_t)(2 * R) * sizeof(double), 256);
   w->off_m = o;        o = align_up(o + (size_t)(2 * R) * sizeof(float), 256);
@@ -105,7 +102,7 @@ static int validate(int dtype, const void* target, const void* draft, const int3
 
 template <typename DT>
 static int launch(Problem p, int stages, hipStream_t stream) {
-  sample_split(p.B, p.V, kBlock * DT::kPerVec, &p.S, &p.chunk);
+  sample_split(p.B, p.V, kSampleTileElems, &p.S, &p.chunk);
   const bool stats = (stages & EARS_STAGE_STATS) != 0;
   const bool decide = (stages & EARS_STAGE_DECIDE) != 0;
   const bool sample = (stages & EARS_STAGE_SAMPLE) != 0;

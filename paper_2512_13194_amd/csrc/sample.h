@@ -10,12 +10,13 @@
 // The winner is the one the fp64 definition gives; fp32 work only discards elements that provably
 // cannot win.  Three levels, each sound with respect to the next:
 //
-//  1. TEST, every element, no transcendental, target row only.  Since w(v) <= p_t(v) and
-//     -log u >= 1 - u, in base-2 logs
-//         score2(v) <= a(v) - log2(1 - u),   a(v) = (l_t(v) - m_t) * log2(e)/T - log2 Z_t
-//     (bonus: a(v) = l_t(v) * log2(e)/T), and log2(x) >= bits(x) * 2^-23 - 127 for a positive
-//     float x.  An element whose bound is below the running threshold theta (a lower bound of the
-//     best score seen so far) is dropped; the rest are queued.
+//  1. TEST, every element, no transcendental, target row only, one Philox block per 16 elements.
+//     u(v) = (h + (f + 1/2) 2^-32) / 256 with h a byte of the "coarse" block; u < (h+1)/256, so
+//     with N = 255 - h, w(v) <= p_t(v) and -log u >= 1 - u > N/256, in base-2 logs
+//         score2(v) <= a(v) + 8 - log2 N,   a(v) = (l_t(v) - m_t) * log2(e)/T - log2 Z_t
+//     (bonus: a(v) = l_t(v) * log2(e)/T), and log2 N >= bits(float(N)) * 2^-23 - 127.  An element
+//     whose bound is below the running threshold theta (a lower bound of the best score seen so
+//     far) is dropped; the rest (all those with N = 0, one in 256, and a few more) are queued.
 //  2. BOUNDS, queued elements, fp32 with explicit margins: s_lo <= score2 <= s_up.  theta rises
 //     to the largest s_lo; an element survives while s_up >= theta.
 //  3. EXACT (select_kernel, one workgroup per sequence): a lone survivor wins as it stands; several
@@ -39,7 +40,6 @@ constexpr float kBonusMargin = 0x1p-10f;       // bonus scores carry l*c itself 
 constexpr float kTestMargin = 0x1p-10f;        // slack of the level-1 test
 constexpr float kDegenerate = -100.0f;         // residual rows whose best lower bound is below
                                                // 2^-100 are scanned in fp64 instead
-constexpr float kLog2Ln2Neg = 0.5287663729448977f;  // -log2(ln 2)
 // "no bound yet".  Finite, and still finite after scaling by 2^23, so that the level-1 bound of a
 // masked or out-of-range element (-inf) never reaches it.
 constexpr float kNoThreshold = -1.0e30f;
@@ -83,8 +83,12 @@ __device__ double exact_score(const SampleCtx& c, int v, int mode) {
       logw = log(pt);
     }
   }
-  const uint32_t w = philox_pick(noise_block(c.seed, c.seq, c.pos, 1u, (uint32_t)v >> 2), (uint32_t)v);
-  const double u = (double)(w >> 9) * 0x1p-23 + 0x1p-24;
+  const uint32_t cw = philox_pick(noise_block(c.seed, c.seq, c.pos, kDomainCoarse, (uint32_t)v >> 4),
+                                  (uint32_t)v >> 2);
+  const uint32_t h = (cw >> (8u * ((uint32_t)v & 3u))) & 0xFFu;
+  const uint32_t f = philox_pick(noise_block(c.seed, c.seq, c.pos, kDomainFine, (uint32_t)v >> 2),
+                                 (uint32_t)v);
+  const double u = ((double)h + ((double)f + 0.5) * 0x1p-32) * 0x1p-8;
   return logw - log(-log(u));
 }
 
@@ -120,7 +124,8 @@ __device__ __forceinline__ int lanes_below(unsigned long long mask) {
 template <typename DT>
 __global__ __launch_bounds__(kBlock) void sample_kernel(Problem p) {
   constexpr int kPer = DT::kPerVec;
-  constexpr int kTile = kBlock * kPer;
+  constexpr int kVecs = kSampleLaneElems / kPer;  // 16-byte loads per lane and tile
+  constexpr int kTile = kSampleTileElems;
   constexpr int kQueueCap = 2 * kWave;  // drained as soon as it holds a full batch
   using storage = typename DT::storage;
 
@@ -168,8 +173,9 @@ __global__ __launch_bounds__(kBlock) void sample_kernel(Problem p) {
     kt = -__builtin_amdgcn_logf((float)p.Z[2 * r]);
     kd = -__builtin_amdgcn_logf((float)p.Z[2 * r + 1]);
   }
+  // level-1 bound, scaled by 2^23: l*cs + ks - bits(float(N)) >= theta * 2^23
   const float cs = c * 0x1p23f;
-  const float ks = (kt + 127.0f + kTestMargin) * 0x1p23f;
+  const float ks = (float)(((double)kt + 135.0 + (double)kTestMargin - (double)mt * (double)c) * 0x1p23);
 
   float theta = kNoThreshold;  // wave-uniform: best proven lower bound of the maximum score (log2)
   int qcount = 0;            // wave-uniform: queued candidates
@@ -182,22 +188,36 @@ __global__ __launch_bounds__(kBlock) void sample_kernel(Problem p) {
     s_lo = -INFINITY;
     const int vv = active ? v : 0;
     const float lt = DT::load(trow, vv);
-    const uint32_t w = philox_pick(noise_block(seed, seq, pos, 1u, (uint32_t)vv >> 2), (uint32_t)vv);
-    const float u = gumbel_uniform_from_word(w);
-    const float e2 = -__builtin_amdgcn_logf(u);                     // -log2 u > 0
-    const float g = kLog2Ln2Neg - __builtin_amdgcn_logf(e2);         // -log2(-ln u)
+    // u = (h + (f + 1/2) 2^-32) / 256 and 1 - u, each to fp32 relative accuracy
+    const uint32_t cw = philox_pick(noise_block(seed, seq, pos, kDomainCoarse, (uint32_t)vv >> 4),
+                                    (uint32_t)vv >> 2);
+    const uint32_t h = (cw >> (8u * ((uint32_t)vv & 3u))) & 0xFFu;
+    const uint32_t f = philox_pick(noise_block(seed, seq, pos, kDomainFine, (uint32_t)vv >> 2),
+                                   (uint32_t)vv);
+    const float u = ((float)h + fmaf((float)f, 0x1p-32f, 0x1p-33f)) * 0x1p-8f;
+    const float om = ((float)(255u - h) + fmaf((float)(~f), 0x1p-32f, 0x1p-33f)) * 0x1p-8f;
+    // E = -ln u bracketed by [e_lo, e_hi]; close to u = 1 from the series of -ln(1 - x)
+    float e_lo, e_hi;
+    if (om < 0x1p-6f) {
+      const float t = fmaf(0.5f, om, 1.0f);
+      e_lo = om * t;                          // x + x^2/2
+      e_hi = om * fmaf(0.5f * om, om, t);     // x + x^2/2 + x^3/2, an upper bound for x <= 1/4
+    } else {
+      e_lo = e_hi = -__builtin_amdgcn_logf(u) * 0.6931471805599453f;
+    }
+    const float g_hi = -__builtin_amdgcn_logf(e_lo);   // -log2(-ln u), from above
+    const float g_lo = -__builtin_amdgcn_logf(e_hi);   //               and from below
     float up, lo;
     if (residual) {
       const float ld = DT::load(drow, vv);
       const float at = fmaf(lt - mt, c, kt), ad = fmaf(ld - md, c, kd);
       const float q_up = __builtin_amdgcn_exp2f(at + kExpMargin) - __builtin_amdgcn_exp2f(ad - kExpMargin);
       const float q_lo = __builtin_amdgcn_exp2f(at - kExpMargin) - __builtin_amdgcn_exp2f(ad + kExpMargin);
-      up = q_up > 0.0f ? __builtin_amdgcn_logf(q_up) + g + kScoreMargin : -INFINITY;
-      lo = q_lo > 0.0f ? __builtin_amdgcn_logf(q_lo) + g - kScoreMargin : -INFINITY;
+      up = q_up > 0.0f ? __builtin_amdgcn_logf(q_up) + g_hi + kScoreMargin : -INFINITY;
+      lo = q_lo > 0.0f ? __builtin_amdgcn_logf(q_lo) + g_lo - kScoreMargin : -INFINITY;
     } else {
-      const float sc = fmaf(lt, c, g);
-      up = sc + kBonusMargin;
-      lo = sc - kBonusMargin;
+      up = fmaf(lt, c, g_hi) + kBonusMargin;
+      lo = fmaf(lt, c, g_lo) - kBonusMargin;
     }
     if (active && up > -INFINITY) { s_up = up; s_lo = lo; }
   };
@@ -246,8 +266,8 @@ __global__ __launch_bounds__(kBlock) void sample_kernel(Problem p) {
   const int v_end = (V - v_begin) < p.chunk ? V : v_begin + p.chunk;
   const bool vector_ok = (reinterpret_cast<uintptr_t>(trow) & 15u) == 0;
 
-  // One 16-byte load per lane and tile; rows that are not 16-byte aligned (or the ragged last
-  // vector) are assembled from element loads into the same packed form, padded with -inf.
+  // One 16-byte load; rows that are not 16-byte aligned (or the ragged last vector) are assembled
+  // from element loads into the same packed form, padded with -inf.
   auto load_raw = [&](int vb) -> uint4 {
     if (vb >= v_end) return DT::neg_inf_vec();
     if (vector_ok && vb + kPer <= v_end) return load_stream(reinterpret_cast<const uint4*>(trow + vb));
@@ -265,7 +285,11 @@ __global__ __launch_bounds__(kBlock) void sample_kernel(Problem p) {
     return make_uint4(wds[0], wds[1], wds[2], wds[3]);
   };
 
-  uint4 raw = load_raw(v_begin + tid * kPer);
+  // a lane owns kSampleLaneElems consecutive entries of each tile: kVecs 16-byte loads and
+  // exactly one coarse Philox block
+  uint4 raw[kVecs];
+#pragma unroll
+  for (int k = 0; k < kVecs; ++k) raw[k] = load_raw(v_begin + tid * kSampleLaneElems + k * kPer);
 
   // warm start: a first threshold from 64 elements of this wave's part of the chunk (their loads
   // travel together with the first tile's)
@@ -277,30 +301,37 @@ __global__ __launch_bounds__(kBlock) void sample_kernel(Problem p) {
   }
 
   for (int tile0 = v_begin; tile0 < v_end; tile0 += kTile) {
-    const int vbase = tile0 + tid * kPer;
-    const uint4 raw_next = load_raw(vbase + kTile);  // in flight while this tile is tested
-    float l[kPer];
-    DT::unpack(raw, l);
-    raw = raw_next;
+    const int vbase = tile0 + tid * kSampleLaneElems;
+    float l[kSampleLaneElems];
+#pragma unroll
+    for (int k = 0; k < kVecs; ++k) {
+      float g[kPer];
+      DT::unpack(raw[k], g);
+#pragma unroll
+      for (int j = 0; j < kPer; ++j) l[k * kPer + j] = g[j];
+      raw[k] = load_raw(vbase + kTile + k * kPer);  // next tile, in flight while this one is tested
+    }
     // level 1
     const float Theta = theta * 0x1p23f;
-    uint32_t mask = 0;
+    const Philox coarse = noise_block(seed, seq, pos, kDomainCoarse, (uint32_t)vbase >> 4);
+    float bound[kSampleLaneElems];
+    float bmax = -INFINITY;
 #pragma unroll
-    for (int g4 = 0; g4 < kPer / 4; ++g4) {
-      const Philox blk = noise_block(seed, seq, pos, 1u, (uint32_t)(vbase >> 2) + (uint32_t)g4);
+    for (int k = 0; k < 4; ++k) {
+      const uint32_t nw = ~coarse.word(k);  // bytes N = 255 - h
 #pragma unroll
-      for (int j4 = 0; j4 < 4; ++j4) {
-        const int j = g4 * 4 + j4;
-        // 1 - u, exact; its bit pattern read as an integer is (log2(1-u) + 127) * 2^23 from below
-        const float one_minus_u = fmaf(-(float)(blk.word(j4) >> 9), 0x1p-23f, 1.0f - 0x1p-24f);
-        const float bound = fmaf(l[j] - mt, cs, ks) - (float)__float_as_int(one_minus_u);
-        if (bound >= Theta) mask |= 1u << j;
+      for (int t = 0; t < 4; ++t) {
+        const int j = 4 * k + t;
+        const float Nf = (float)((nw >> (8 * t)) & 0xFFu);
+        // the bit pattern of float(N), read as an integer, is (log2 N + 127) * 2^23 from below
+        bound[j] = fmaf(l[j], cs, ks) - (float)__float_as_int(Nf);
+        bmax = fmaxf(bmax, bound[j]);
       }
     }
-    if (__ballot(mask != 0u) != 0ull) {
+    if (__ballot(bmax >= Theta) != 0ull) {
 #pragma unroll
-      for (int j = 0; j < kPer; ++j) {
-        const bool pj = (mask >> j) & 1u;
+      for (int j = 0; j < kSampleLaneElems; ++j) {
+        const bool pj = bound[j] >= Theta;
         const unsigned long long bal = __ballot(pj);
         if (bal != 0ull) {
           if (pj) sh_queue[wave][qcount + lanes_below(bal)] = vbase + j;
