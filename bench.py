@@ -55,6 +55,9 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=40)
     ap.add_argument("--warmup", type=int, default=8)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--traffic-calibration", action="store_true",
+                    help="also run the plain copy kernel over a buffer of known size (for scaling "
+                         "rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         log("bench.py: this build runs on ONE GPU; sequences are independent, so more GPUs would "
@@ -111,28 +114,27 @@ def main() -> int:
     call_bytes = k1_bytes + (2 * mean_rej + (B - mean_rej)) * V * esz
     call_gbps = call_bytes / (ms_per_step * 1e-3) / 1e9
 
-    # dominant kernel: the row-statistics pass.  Its duration is measured with HIP events on the
-    # stream it is launched on, stage by stage, over the same number of steps.
+    # dominant kernel: the row-statistics pass.  Its average launch duration is measured with HIP
+    # events on the stream it is launched on (torch's current stream, which the binding passes to
+    # the library): `steps` launches of the statistics stage back to back between two events, so
+    # that the events' own cost is spread over all of them.
     ws = torch.empty(ears.ears_workspace_bytes(B * K, B, V), dtype=torch.uint8, device="cuda")
-    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
-          for _ in range(args.steps)]
-    for i in range(max(2, args.warmup // 2)):
-        ears.ears_verify_ex(batch.target, batch.draft, batch.tokens, temperature=T, beta=betas[0],
-                            seed=seed0, workspace=ws, stages=ears.EARS_STAGE_STATS,
-                            out_accept_len=acc, out_tokens=tok.view(-1))
-    torch.cuda.synchronize()
-    for i in range(args.steps):
-        ev[i][0].record()
+
+    def stats_only(i):
         ears.ears_verify_ex(batch.target, batch.draft, batch.tokens, temperature=T, beta=betas[0],
                             seed=seed0 + i, workspace=ws, stages=ears.EARS_STAGE_STATS,
                             out_accept_len=acc, out_tokens=tok.view(-1))
-        ev[i][1].record()
-        ears.ears_verify_ex(batch.target, batch.draft, batch.tokens, temperature=T,
-                            beta=betas[i % len(betas)], seed=seed0 + i, workspace=ws,
-                            stages=ears.EARS_STAGE_DECIDE | ears.EARS_STAGE_SAMPLE,
-                            out_accept_len=acc, out_tokens=tok.view(-1))
+
+    for i in range(max(2, args.warmup // 2)):
+        stats_only(i)
     torch.cuda.synchronize()
-    k1_ms = sum(a.elapsed_time(b) for a, b in ev) / args.steps
+    k0, k1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    k0.record()
+    for i in range(args.steps):
+        stats_only(i)
+    k1.record()
+    torch.cuda.synchronize()
+    k1_ms = k0.elapsed_time(k1) / args.steps
     k1_gbps = k1_bytes / (k1_ms * 1e-3) / 1e9
 
     # practical ceiling: a read-only streaming kernel over the same two buffers
@@ -150,6 +152,15 @@ def main() -> int:
     torch.cuda.synchronize()
     read_bytes = (batch.target.numel() + batch.draft.numel()) * esz
     read_gbps = read_bytes * reps / (e0.elapsed_time(e1) * 1e-3) / 1e9
+
+    if args.traffic_calibration:
+        # plain copy of the draft buffer: reads and writes exactly draft.numel() * 2 bytes
+        dst = torch.empty_like(batch.draft)
+        for _ in range(4):
+            ears.ears_bench_copy(dst, batch.draft)
+        torch.cuda.synchronize()
+        log("traffic calibration: ears_bench_copy of %d bytes, 4 times" % (batch.draft.numel() * esz))
+        del dst
 
     cpu = None
     if not args.no_cpu_baseline:

@@ -9,19 +9,28 @@ namespace ears {
 // Measurement aids.
 // =================================================================================================
 constexpr int kBenchBlocks = 4096;
+constexpr size_t kBenchSlabVecs = 16384;  // 256 KiB per workgroup visit, about one logit row
 
+// Read-only ceiling: every workgroup streams whole 256 KiB slabs with the same non-temporal
+// 16-byte loads, eight in flight per lane, that the row-statistics pass uses, and folds them
+// into a checksum.
 __global__ __launch_bounds__(kBlock) void bench_read_kernel(const uint4* src, size_t nvec,
                                                             uint32_t* sink) {
   uint32_t acc = 0;
-  const size_t stride = (size_t)gridDim.x * kBlock;
-  size_t i = (size_t)blockIdx.x * kBlock + threadIdx.x;
-  for (; i + 3 * stride < nvec; i += 4 * stride) {
-    const uint4 a = src[i], b = src[i + stride], c = src[i + 2 * stride], d = src[i + 3 * stride];
-    acc ^= a.x ^ a.y ^ a.z ^ a.w ^ b.x ^ b.y ^ b.z ^ b.w ^ c.x ^ c.y ^ c.z ^ c.w ^ d.x ^ d.y ^ d.z ^ d.w;
-  }
-  for (; i < nvec; i += stride) {
-    const uint4 a = src[i];
-    acc ^= a.x ^ a.y ^ a.z ^ a.w;
+  const size_t nslabs = (nvec + kBenchSlabVecs - 1) / kBenchSlabVecs;
+  for (size_t slab = blockIdx.x; slab < nslabs; slab += gridDim.x) {
+    const size_t v0 = slab * kBenchSlabVecs;
+    const size_t v1 = v0 + kBenchSlabVecs < nvec ? v0 + kBenchSlabVecs : nvec;
+    for (size_t i0 = v0 + threadIdx.x; i0 < v1; i0 += (size_t)kBlock * 8) {
+      uint4 raw[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const size_t i = i0 + (size_t)u * kBlock;
+        raw[u] = i < v1 ? load_stream(src + i) : make_uint4(0u, 0u, 0u, 0u);
+      }
+#pragma unroll
+      for (int u = 0; u < 8; ++u) acc ^= raw[u].x ^ raw[u].y ^ raw[u].z ^ raw[u].w;
+    }
   }
 #pragma unroll
   for (int d = 1; d < kWave; d <<= 1) acc ^= __shfl_xor(acc, d, 64);

@@ -9,9 +9,11 @@ namespace ears {
 
 // Decision for draft position i of sequence b (packed row r) from the row statistics: row maximum
 // m, Z = sum exp((l-m)/T) and the draft token's logit lx, for the target (t) and draft (d) rows.
-// Evaluated in fp64, so the outcome does not depend on fp32 rounding of R or the threshold.
-// Returns 0 reject, 1 accepted by R >= U, 2 accepted only through the tolerance.  Writes the
-// optional per-position statistics / branch id and raises the status bit for an invalid token.
+// Evaluated in fp64 whenever fp32 could not tell, so the outcome does not depend on fp32 rounding
+// of R or the threshold.  Returns 0 reject, 1 accepted by R >= U, 2 accepted only through the
+// tolerance (1 for either kind of acceptance when neither statistics nor branch ids are asked
+// for).  Writes the optional per-position statistics / branch id and raises the status bit for
+// an invalid token.
 __device__ __forceinline__ int decide_position(const Problem& p, int b, int i, int64_t r, double mt,
                                                double Zt, double lxt, double md, double Zd,
                                                double lxd) {
@@ -19,6 +21,22 @@ __device__ __forceinline__ int decide_position(const Problem& p, int b, int i, i
   const double beta = (double)seq_beta(p, b);
   const int32_t x = p.tokens[r];
   const bool valid = x >= 0 && x < p.V;
+  if (valid && !p.out_stats && !p.out_path) {
+    // Most decisions are far from the threshold: settle those in fp32 with a margin that covers
+    // its rounding many times over (1e-4 relative on R, 1e-6 (1 + beta) absolute on the
+    // threshold) and leave only the close calls and the guarded division to fp64.
+    const float cf = (float)(kLog2e / T);
+    const float Ptf = __builtin_amdgcn_exp2f(((float)lxt - (float)mt) * cf) / (float)Zt;
+    const float Pdf = __builtin_amdgcn_exp2f(((float)lxd - (float)md) * cf) / (float)Zd;
+    if (Pdf > 1e-9f) {
+      const float Rf = Ptf / Pdf;
+      const float Uf = (float)accept_uniform(p.seed, seq_rng_id(p, b), (uint32_t)i);
+      const float thrf = fmaxf(Uf - (float)beta * (1.0f - 1.0f / (float)Zt), 0.0f);
+      const float slack = 1e-6f * (1.0f + (float)beta);
+      if (Rf * (1.0f - 1e-4f) > thrf + slack) return 1;
+      if (Rf * (1.0f + 1e-4f) < thrf - slack) return 0;
+    }
+  }
   const double Ptx = valid ? exp((lxt - mt) / T) / Zt : 0.0;
   const double Pdx = valid ? exp((lxd - md) / T) / Zd : 0.0;
   const double R = Ptx / fmax(Pdx, kEpsilon);                              // step 2, division guard

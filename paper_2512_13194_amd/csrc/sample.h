@@ -129,7 +129,8 @@ __global__ __launch_bounds__(kBlock) void sample_kernel(Problem p) {
   constexpr int kQueueCap = 2 * kWave;  // drained as soon as it holds a full batch
   using storage = typename DT::storage;
 
-  __shared__ int sh_queue[kWavesPerBlock][kQueueCap];
+  __shared__ int sh_queue[kWavesPerBlock][kQueueCap];    // queued vocabulary indices ...
+  __shared__ int sh_queue_h[kWavesPerBlock][kQueueCap];  // ... and their coarse noise bytes
   __shared__ int sh_surv_v[kWavesPerBlock][kSurvivorCap];
   __shared__ float sh_surv_s[kWavesPerBlock][kSurvivorCap];
   __shared__ float sh_theta[kWavesPerBlock];
@@ -182,16 +183,20 @@ __global__ __launch_bounds__(kBlock) void sample_kernel(Problem p) {
   int scount = 0;            // wave-uniform: survivors of this wave
   bool overflow = false;
 
-  // Level 2 for up to 64 queued elements, one per lane.
-  auto evaluate = [&](int v, bool active, float& s_up, float& s_lo) {
+  // Level 2 for up to 64 queued elements, one per lane.  h_known is the element's coarse noise
+  // byte when the caller has it (queued elements), -1 when it has to be generated here.
+  auto evaluate = [&](int v, int h_known, bool active, float& s_up, float& s_lo) {
     s_up = -INFINITY;
     s_lo = -INFINITY;
     const int vv = active ? v : 0;
     const float lt = DT::load(trow, vv);
     // u = (h + (f + 1/2) 2^-32) / 256 and 1 - u, each to fp32 relative accuracy
-    const uint32_t cw = philox_pick(noise_block(seed, seq, pos, kDomainCoarse, (uint32_t)vv >> 4),
-                                    (uint32_t)vv >> 2);
-    const uint32_t h = (cw >> (8u * ((uint32_t)vv & 3u))) & 0xFFu;
+    uint32_t h = (uint32_t)h_known;
+    if (h_known < 0) {
+      const uint32_t cw = philox_pick(noise_block(seed, seq, pos, kDomainCoarse, (uint32_t)vv >> 4),
+                                      (uint32_t)vv >> 2);
+      h = (cw >> (8u * ((uint32_t)vv & 3u))) & 0xFFu;
+    }
     const uint32_t f = philox_pick(noise_block(seed, seq, pos, kDomainFine, (uint32_t)vv >> 2),
                                    (uint32_t)vv);
     const float u = ((float)h + fmaf((float)f, 0x1p-32f, 0x1p-33f)) * 0x1p-8f;
@@ -207,14 +212,19 @@ __global__ __launch_bounds__(kBlock) void sample_kernel(Problem p) {
     }
     const float g_hi = -__builtin_amdgcn_logf(e_lo);   // -log2(-ln u), from above
     const float g_lo = -__builtin_amdgcn_logf(e_hi);   //               and from below
-    float up, lo;
+    float up = -INFINITY, lo = -INFINITY;
     if (residual) {
-      const float ld = DT::load(drow, vv);
-      const float at = fmaf(lt - mt, c, kt), ad = fmaf(ld - md, c, kd);
-      const float q_up = __builtin_amdgcn_exp2f(at + kExpMargin) - __builtin_amdgcn_exp2f(ad - kExpMargin);
-      const float q_lo = __builtin_amdgcn_exp2f(at - kExpMargin) - __builtin_amdgcn_exp2f(ad + kExpMargin);
-      up = q_up > 0.0f ? __builtin_amdgcn_logf(q_up) + g_hi + kScoreMargin : -INFINITY;
-      lo = q_lo > 0.0f ? __builtin_amdgcn_logf(q_lo) + g_lo - kScoreMargin : -INFINITY;
+      // with p_d = 0 the score could be at most a(v) + g: only lanes that can still reach theta
+      // that way fetch the draft logit (a scattered access) and evaluate the residual
+      const float at = fmaf(lt - mt, c, kt);
+      if (active && at + kExpMargin + g_hi + kScoreMargin >= theta) {
+        const float ld = DT::load(drow, vv);
+        const float ad = fmaf(ld - md, c, kd);
+        const float q_up = __builtin_amdgcn_exp2f(at + kExpMargin) - __builtin_amdgcn_exp2f(ad - kExpMargin);
+        const float q_lo = __builtin_amdgcn_exp2f(at - kExpMargin) - __builtin_amdgcn_exp2f(ad + kExpMargin);
+        up = q_up > 0.0f ? __builtin_amdgcn_logf(q_up) + g_hi + kScoreMargin : -INFINITY;
+        lo = q_lo > 0.0f ? __builtin_amdgcn_logf(q_lo) + g_lo - kScoreMargin : -INFINITY;
+      }
     } else {
       up = fmaf(lt, c, g_hi) + kBonusMargin;
       lo = fmaf(lt, c, g_lo) - kBonusMargin;
@@ -243,9 +253,10 @@ __global__ __launch_bounds__(kBlock) void sample_kernel(Problem p) {
     const bool active = lane < cnt;
     __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
     const int v = active ? sh_queue[wave][qcount - cnt + lane] : 0;
+    const int h = active ? sh_queue_h[wave][qcount - cnt + lane] : 0;
     qcount -= cnt;
     float s_up, s_lo;
-    evaluate(v, active, s_up, s_lo);
+    evaluate(v, h, active, s_up, s_lo);
     theta = fmaxf(theta, wave_max(s_lo));
     const bool surv = active && s_up > -INFINITY && s_up >= theta;
     const unsigned long long sm = __ballot(surv);
@@ -267,10 +278,12 @@ __global__ __launch_bounds__(kBlock) void sample_kernel(Problem p) {
   const bool vector_ok = (reinterpret_cast<uintptr_t>(trow) & 15u) == 0;
 
   // One 16-byte load; rows that are not 16-byte aligned (or the ragged last vector) are assembled
-  // from element loads into the same packed form, padded with -inf.
+  // from element loads into the same packed form, padded with -inf.  Ordinary cached loads: a
+  // lane's loads of one tile are adjacent 16-byte pieces of the same cache lines, which
+  // non-temporal loads would fetch from memory once per piece (1.6x the row's bytes, measured).
   auto load_raw = [&](int vb) -> uint4 {
     if (vb >= v_end) return DT::neg_inf_vec();
-    if (vector_ok && vb + kPer <= v_end) return load_stream(reinterpret_cast<const uint4*>(trow + vb));
+    if (vector_ok && vb + kPer <= v_end) return *reinterpret_cast<const uint4*>(trow + vb);
     uint32_t wds[4];
 #pragma unroll
     for (int d = 0; d < 4; ++d) {
@@ -296,7 +309,7 @@ __global__ __launch_bounds__(kBlock) void sample_kernel(Problem p) {
   {
     const int v = v_begin + wave * kWave + lane;
     float s_up, s_lo;
-    evaluate(v, v < v_end, s_up, s_lo);
+    evaluate(v, -1, v < v_end, s_up, s_lo);
     theta = fmaxf(theta, wave_max(s_lo));
   }
 
@@ -315,14 +328,15 @@ __global__ __launch_bounds__(kBlock) void sample_kernel(Problem p) {
     const float Theta = theta * 0x1p23f;
     const Philox coarse = noise_block(seed, seq, pos, kDomainCoarse, (uint32_t)vbase >> 4);
     float bound[kSampleLaneElems];
+    uint32_t nw[4];
     float bmax = -INFINITY;
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
-      const uint32_t nw = ~coarse.word(k);  // bytes N = 255 - h
+      nw[k] = ~coarse.word(k);  // bytes N = 255 - h
 #pragma unroll
       for (int t = 0; t < 4; ++t) {
         const int j = 4 * k + t;
-        const float Nf = (float)((nw >> (8 * t)) & 0xFFu);
+        const float Nf = (float)((nw[k] >> (8 * t)) & 0xFFu);
         // the bit pattern of float(N), read as an integer, is (log2 N + 127) * 2^23 from below
         bound[j] = fmaf(l[j], cs, ks) - (float)__float_as_int(Nf);
         bmax = fmaxf(bmax, bound[j]);
@@ -334,7 +348,11 @@ __global__ __launch_bounds__(kBlock) void sample_kernel(Problem p) {
         const bool pj = bound[j] >= Theta;
         const unsigned long long bal = __ballot(pj);
         if (bal != 0ull) {
-          if (pj) sh_queue[wave][qcount + lanes_below(bal)] = vbase + j;
+          if (pj) {
+            const int slot = qcount + lanes_below(bal);
+            sh_queue[wave][slot] = vbase + j;
+            sh_queue_h[wave][slot] = (int)(255u - ((nw[j >> 2] >> (8 * (j & 3))) & 0xFFu));
+          }
           qcount += __popcll(bal);
           if (qcount >= kWave) evaluate_batch(kWave);
         }
