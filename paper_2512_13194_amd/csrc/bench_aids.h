@@ -37,7 +37,11 @@ __global__ __launch_bounds__(kBlock) void bench_read_kernel(const uint4* src, si
   __shared__ uint32_t sh[kWavesPerBlock];
   if ((threadIdx.x & (kWave - 1)) == 0) sh[threadIdx.x / kWave] = acc;
   __syncthreads();
-  if (threadIdx.x == 0) sink[blockIdx.x] = sh[0] ^ sh[1] ^ sh[2] ^ sh[3];
+  if (threadIdx.x == 0) {
+    uint32_t x = 0;
+    for (int w = 0; w < kWavesPerBlock; ++w) x ^= sh[w];
+    sink[blockIdx.x] = x;
+  }
 }
 
 __global__ __launch_bounds__(kBlock) void bench_copy_kernel(uint4* dst, const uint4* src,

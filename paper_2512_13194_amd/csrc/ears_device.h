@@ -7,7 +7,7 @@
 namespace ears {
 
 constexpr int kWave = 64;
-constexpr int kBlock = 256;             // threads per workgroup: 4 waves
+constexpr int kBlock = 512;             // threads per workgroup: 8 waves
 constexpr int kWavesPerBlock = kBlock / kWave;
 
 constexpr double kLog2e = 1.4426950408889634074;

@@ -45,7 +45,7 @@ static size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 // workgroups exist.  The filter is bound by vector-ALU issue (Philox), so more, shorter
 // workgroups only add their fixed prologue cost: 512-2048 groups measure within 10% of each
 // other on 256 CUs, 1024 best.
-constexpr int kSampleTargetGroups = 1024;
+constexpr int kSampleTargetGroups = 512;
 
 static void sample_split(int B, int V, int elems_per_tile, int* S, int* chunk) {
   const int ntiles = (V + elems_per_tile - 1) / elems_per_tile;

@@ -80,7 +80,7 @@ __device__ __forceinline__ void row_pass(const typename DT::storage* base, int V
     accumulate<kUnroll * kPer>(f, c, m_run, mc, S);
   }
 
-  // merge the 256 lanes
+  // merge the lanes of the workgroup
   const int lane = tid & (kWave - 1), wave = tid / kWave;
   const float wm = wave_max(m_run);
   __syncthreads();  // the previous pass has finished with the shared arrays
