@@ -9,27 +9,28 @@ namespace ears {
 // Measurement aids.
 // =================================================================================================
 constexpr int kBenchBlocks = 4096;
-constexpr size_t kBenchSlabVecs = 16384;  // 256 KiB per workgroup visit, about one logit row
+constexpr size_t kBenchSlabVecs = 16384;  // about 256 KiB per workgroup visit, one logit row
+constexpr int kBenchUnroll = 4;           // 16-byte loads in flight per lane, as in the row pass
 
 // Read-only ceiling: every workgroup streams whole 256 KiB slabs with the same non-temporal
-// 16-byte loads, eight in flight per lane, that the row-statistics pass uses, and folds them
+// 16-byte loads, four in flight per lane, that the row-statistics pass uses, and folds them
 // into a checksum.
 __global__ __launch_bounds__(kBlock) void bench_read_kernel(const uint4* src, size_t nvec,
-                                                            uint32_t* sink) {
+                                                            size_t slab_vecs, uint32_t* sink) {
   uint32_t acc = 0;
-  const size_t nslabs = (nvec + kBenchSlabVecs - 1) / kBenchSlabVecs;
+  const size_t nslabs = (nvec + slab_vecs - 1) / slab_vecs;
   for (size_t slab = blockIdx.x; slab < nslabs; slab += gridDim.x) {
-    const size_t v0 = slab * kBenchSlabVecs;
-    const size_t v1 = v0 + kBenchSlabVecs < nvec ? v0 + kBenchSlabVecs : nvec;
-    for (size_t i0 = v0 + threadIdx.x; i0 < v1; i0 += (size_t)kBlock * 8) {
-      uint4 raw[8];
+    const size_t v0 = slab * slab_vecs;
+    const size_t v1 = v0 + slab_vecs < nvec ? v0 + slab_vecs : nvec;
+    for (size_t i0 = v0 + threadIdx.x; i0 < v1; i0 += (size_t)kBlock * kBenchUnroll) {
+      uint4 raw[kBenchUnroll];
 #pragma unroll
-      for (int u = 0; u < 8; ++u) {
+      for (int u = 0; u < kBenchUnroll; ++u) {
         const size_t i = i0 + (size_t)u * kBlock;
         raw[u] = i < v1 ? load_stream(src + i) : make_uint4(0u, 0u, 0u, 0u);
       }
 #pragma unroll
-      for (int u = 0; u < 8; ++u) acc ^= raw[u].x ^ raw[u].y ^ raw[u].z ^ raw[u].w;
+      for (int u = 0; u < kBenchUnroll; ++u) acc ^= raw[u].x ^ raw[u].y ^ raw[u].z ^ raw[u].w;
     }
   }
 #pragma unroll

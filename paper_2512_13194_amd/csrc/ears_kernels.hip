@@ -306,9 +306,15 @@ int ears_bench_read(const void* src, size_t bytes, uint32_t* sink, void* stream)
   if (!src || !sink) return EARS_ERR_NULL;
   if (bytes == 0 || bytes % 16 != 0) return EARS_ERR_SHAPE;
   if (!aligned(src, 16) || !aligned(sink, 4)) return EARS_ERR_ALIGN;
+  // slabs of about 256 KiB, their number a multiple of 1024 (four 512-thread workgroups on each
+  // of 256 CUs) so that the last round of workgroups is a full one
+  const size_t nvec = bytes / 16;
+  size_t rounds = (nvec + 1024 * kBenchSlabVecs / 2) / (1024 * kBenchSlabVecs);
+  if (rounds < 1) rounds = 1;
+  const size_t slab_vecs = (nvec + 1024 * rounds - 1) / (1024 * rounds);
   hipLaunchKernelGGL(bench_read_kernel, dim3(kBenchBlocks), dim3(kBlock), 0,
-                     static_cast<hipStream_t>(stream), static_cast<const uint4*>(src), bytes / 16,
-                     sink);
+                     static_cast<hipStream_t>(stream), static_cast<const uint4*>(src), nvec,
+                     slab_vecs, sink);
   return hipGetLastError() == hipSuccess ? EARS_OK : EARS_ERR_HIP;
 }
 
