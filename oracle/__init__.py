@@ -7,6 +7,9 @@ from .ears_oracle import (  # noqa: F401
     NDIAG,
     NSAMP,
     OracleResult,
+    UNC_ENTROPY,
+    UNC_MAXPROB,
+    entropy,
     accept_uniform,
     build,
     gumbel,

@@ -127,8 +127,16 @@ static void top2_push(top2_t* t, double s, int32_t v) {
   }
 }
 
+/* Shannon entropy of a probability vector in nats, -sum p log p over p > 0. */
+double ears_oracle_entropy(const double* p, int V) {
+  double H = 0.0;
+  for (int v = 0; v < V; ++v)
+    if (p[v] > 0.0) H -= p[v] * log(p[v]);
+  return H;
+}
+
 int ears_oracle_verify_seq(const void* target_rows, const void* draft_rows, const int32_t* tokens,
-                           int dtype, int K, int V, double T, double beta, uint64_t seed,
+                           int dtype, int K, int V, double T, double beta, int unc_mode, uint64_t seed,
                            uint64_t seq_id, int32_t* accept_len, int32_t* out_tokens, double* diag,
                            int32_t* path, double* samp) {
   int rc = 0;
@@ -151,8 +159,11 @@ int ears_oracle_verify_seq(const void* target_rows, const void* draft_rows, cons
     double R = Ptx / Pd_safe;
     /* step 3 */
     double U = ears_oracle_accept_uniform(seed, seq_id, (uint32_t)i);
-    /* step 4: uncertainty 1 - max P_t and tolerance beta * uncertainty (Section 3.2) */
+    /* step 4: uncertainty 1 - max P_t and tolerance beta * uncertainty (Section 3.2); the
+     * alternative measure (Section 5, "distribution entropy") is the Shannon entropy of P_t
+     * divided by its largest possible value log V */
     double unc = 1.0 - maxpt;
+    if (unc_mode == EARS_ORACLE_UNC_ENTROPY) unc = (V > 1) ? ears_oracle_entropy(pt, V) / log((double)V) : 0.0;
     double tol = beta * unc;
     /* threshold clamp of Section 3.3 item 2 */
     double thr = U - tol;
@@ -236,7 +247,7 @@ int ears_oracle_verify_seq(const void* target_rows, const void* draft_rows, cons
 }
 
 int ears_oracle_verify(const void* target, const void* draft, const int32_t* tokens, int dtype,
-                       int B, int K, int V, double T, double beta, uint64_t seed,
+                       int B, int K, int V, double T, double beta, int unc_mode, uint64_t seed,
                        const int64_t* seq_ids, int32_t* accept_len, int32_t* out_tokens,
                        double* diag, int32_t* path, double* samp, int nthreads) {
   int rc = 0;
@@ -246,7 +257,7 @@ int ears_oracle_verify(const void* target, const void* draft, const int32_t* tok
     uint64_t seq = seq_ids ? (uint64_t)seq_ids[b] : (uint64_t)b;
     rc |= ears_oracle_verify_seq(
         row_ptr(target, dtype, (int64_t)b * (K + 1), V), row_ptr(draft, dtype, (int64_t)b * K, V),
-        tokens + (size_t)b * K, dtype, K, V, T, beta, seed, seq, accept_len + b,
+        tokens + (size_t)b * K, dtype, K, V, T, beta, unc_mode, seed, seq, accept_len + b,
         out_tokens + (size_t)b * (K + 1), diag ? diag + (size_t)b * K * EARS_ORACLE_NDIAG : NULL,
         path ? path + (size_t)b * K : NULL, samp ? samp + (size_t)b * EARS_ORACLE_NSAMP : NULL);
   }
@@ -255,7 +266,7 @@ int ears_oracle_verify(const void* target, const void* draft, const int32_t* tok
 
 int ears_oracle_verify_ragged(const void* target, const void* draft, const int32_t* tokens,
                               const int64_t* row_offsets, int dtype, int B, int V, const float* T,
-                              const float* beta, uint64_t seed, const int64_t* seq_ids,
+                              const float* beta, int unc_mode, uint64_t seed, const int64_t* seq_ids,
                               int32_t* accept_len, int32_t* out_tokens, double* diag,
                               int32_t* path, double* samp, int nthreads) {
   int rc = 0;
@@ -267,7 +278,7 @@ int ears_oracle_verify_ragged(const void* target, const void* draft, const int32
     uint64_t seq = seq_ids ? (uint64_t)seq_ids[b] : (uint64_t)b;
     rc |= ears_oracle_verify_seq(
         row_ptr(target, dtype, r0 + b, V), row_ptr(draft, dtype, r0, V), tokens + r0, dtype, Kb, V,
-        (double)T[b], (double)beta[b], seed, seq, accept_len + b, out_tokens + r0 + b,
+        (double)T[b], (double)beta[b], unc_mode, seed, seq, accept_len + b, out_tokens + r0 + b,
         diag ? diag + (size_t)r0 * EARS_ORACLE_NDIAG : NULL, path ? path + r0 : NULL,
         samp ? samp + (size_t)b * EARS_ORACLE_NSAMP : NULL);
   }

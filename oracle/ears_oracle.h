@@ -39,6 +39,7 @@ extern "C" {
  *   0 m_t   max target logit                      5 P_d(x)  draft probability of the draft token
  *   1 Z_t   sum_v exp((l_t[v]-m_t)/T)             6 unc     1 - max_v P_t(v)   (Section 3.2)
  *   2 P_t(x) target probability of draft token    7 R       P_t(x) / max(P_d(x), 1e-10)
+ *     (or H(P_t)/log V when the entropy measure is selected)
  *   3 m_d   max draft logit                       8 U       acceptance uniform in [0,1)
  *   4 Z_d   draft sum-exp                         9 thr     max(U - beta*unc, 0)   (Section 3.3)
  */
@@ -49,6 +50,11 @@ extern "C" {
  *   2 gap = best - second, 3 mode (0 residual, 1 bonus, 2 residual empty -> target-row fallback)
  */
 #define EARS_ORACLE_NSAMP 4
+
+/* uncertainty measure that scales the tolerance: the paper's 1 - max P_t (Section 3.2), or the
+ * normalised Shannon entropy H(P_t) / log V (the "distribution entropy" of Section 5) */
+#define EARS_ORACLE_UNC_MAXPROB 0
+#define EARS_ORACLE_UNC_ENTROPY 1
 
 /* One Philox4x32-10 block: 10 rounds on a 128-bit counter with a 64-bit key. */
 void ears_oracle_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4]);
@@ -77,6 +83,9 @@ double ears_oracle_gumbel(uint64_t seed, uint64_t seq, uint32_t pos, uint32_t v)
 double ears_oracle_softmax(const void* row, int dtype, int V, double T, double* p, double* m,
                            double* Z);
 
+/* Shannon entropy -sum p log p (nats) of a probability vector. */
+double ears_oracle_entropy(const double* p, int V);
+
 /* Verify one sequence.
  *   target_rows [K+1, V], draft_rows [K, V] row-major logits of type dtype
  *   tokens [K] draft tokens (a token outside [0,V) is rejected at its position)
@@ -86,7 +95,7 @@ double ears_oracle_softmax(const void* row, int dtype, int V, double T, double* 
  *   samp [EARS_ORACLE_NSAMP] (may be NULL)
  * Returns 0, or 1 if some draft token was out of range. */
 int ears_oracle_verify_seq(const void* target_rows, const void* draft_rows, const int32_t* tokens,
-                           int dtype, int K, int V, double T, double beta, uint64_t seed,
+                           int dtype, int K, int V, double T, double beta, int unc_mode, uint64_t seed,
                            uint64_t seq_id, int32_t* accept_len, int32_t* out_tokens, double* diag,
                            int32_t* path, double* samp);
 
@@ -95,7 +104,7 @@ int ears_oracle_verify_seq(const void* target_rows, const void* draft_rows, cons
  * that many OpenMP threads (the arithmetic per sequence is unchanged).
  * Returns the OR of the per-sequence return codes. */
 int ears_oracle_verify(const void* target, const void* draft, const int32_t* tokens, int dtype,
-                       int B, int K, int V, double T, double beta, uint64_t seed,
+                       int B, int K, int V, double T, double beta, int unc_mode, uint64_t seed,
                        const int64_t* seq_ids, int32_t* accept_len, int32_t* out_tokens,
                        double* diag, int32_t* path, double* samp, int nthreads);
 
@@ -105,7 +114,7 @@ int ears_oracle_verify(const void* target, const void* draft, const int32_t* tok
  * target rows.  T[b] and beta[b] are per sequence. */
 int ears_oracle_verify_ragged(const void* target, const void* draft, const int32_t* tokens,
                               const int64_t* row_offsets, int dtype, int B, int V, const float* T,
-                              const float* beta, uint64_t seed, const int64_t* seq_ids,
+                              const float* beta, int unc_mode, uint64_t seed, const int64_t* seq_ids,
                               int32_t* accept_len, int32_t* out_tokens, double* diag,
                               int32_t* path, double* samp, int nthreads);
 

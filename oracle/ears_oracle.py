@@ -61,14 +61,16 @@ def _load():
     lib.ears_oracle_softmax.argtypes = [c.c_void_p, c.c_int, c.c_int, c.c_double, c.c_void_p,
                                         c.POINTER(c.c_double), c.POINTER(c.c_double)]
     lib.ears_oracle_softmax.restype = c.c_double
+    lib.ears_oracle_entropy.argtypes = [c.c_void_p, c.c_int]
+    lib.ears_oracle_entropy.restype = c.c_double
     lib.ears_oracle_verify.argtypes = [
         c.c_void_p, c.c_void_p, c.c_void_p, c.c_int, c.c_int, c.c_int, c.c_int, c.c_double,
-        c.c_double, c.c_uint64, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p,
+        c.c_double, c.c_int, c.c_uint64, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p,
         c.c_void_p, c.c_int]
     lib.ears_oracle_verify.restype = c.c_int
     lib.ears_oracle_verify_ragged.argtypes = [
         c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_int, c.c_int, c.c_int, c.c_void_p,
-        c.c_void_p, c.c_uint64, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p,
+        c.c_void_p, c.c_int, c.c_uint64, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p,
         c.c_void_p, c.c_int]
     lib.ears_oracle_verify_ragged.restype = c.c_int
     _lib = lib
@@ -138,8 +140,18 @@ class OracleResult:
         return self.diag[..., DIAG_NAMES.index(name)]
 
 
+UNC_MAXPROB, UNC_ENTROPY = 0, 1
+
+
+def entropy(p: np.ndarray) -> float:
+    """Shannon entropy (nats) of a float64 probability vector."""
+    p = np.ascontiguousarray(p, dtype=np.float64)
+    return float(_load().ears_oracle_entropy(_ptr(p), p.shape[0]))
+
+
 def verify(target: np.ndarray, draft: np.ndarray, tokens: np.ndarray, T: float, beta: float,
-           seed: int, seq_ids: Optional[np.ndarray] = None, nthreads: int = 1) -> OracleResult:
+           seed: int, seq_ids: Optional[np.ndarray] = None, nthreads: int = 1,
+           uncertainty: int = UNC_MAXPROB) -> OracleResult:
     """target [B, K+1, V], draft [B, K, V] (float32 or uint16 bf16 bits), tokens [B, K] int32."""
     lib = _load()
     target = np.ascontiguousarray(target)
@@ -158,14 +170,15 @@ def verify(target: np.ndarray, draft: np.ndarray, tokens: np.ndarray, T: float, 
     path = np.empty((B, K), dtype=np.int32)
     samp = np.empty((B, NSAMP), dtype=np.float64)
     rc = lib.ears_oracle_verify(_ptr(target), _ptr(draft), _ptr(tokens), _dtype_code(target), B, K,
-                                V, float(T), float(beta), int(seed), _ptr(seq_ids), _ptr(acc),
+                                V, float(T), float(beta), int(uncertainty), int(seed), _ptr(seq_ids), _ptr(acc),
                                 _ptr(out), _ptr(diag), _ptr(path), _ptr(samp), int(nthreads))
     return OracleResult(acc, out, diag, path, samp, int(rc))
 
 
 def verify_ragged(target: np.ndarray, draft: np.ndarray, tokens: np.ndarray,
                   row_offsets: np.ndarray, T: np.ndarray, beta: np.ndarray, seed: int,
-                  seq_ids: Optional[np.ndarray] = None, nthreads: int = 1) -> OracleResult:
+                  seq_ids: Optional[np.ndarray] = None, nthreads: int = 1,
+                  uncertainty: int = UNC_MAXPROB) -> OracleResult:
     """target [R + B, V], draft [R, V], tokens [R]; row_offsets [B+1] int64 over draft rows."""
     lib = _load()
     target = np.ascontiguousarray(target)
@@ -188,7 +201,7 @@ def verify_ragged(target: np.ndarray, draft: np.ndarray, tokens: np.ndarray,
     path = np.empty(R, dtype=np.int32)
     samp = np.empty((B, NSAMP), dtype=np.float64)
     rc = lib.ears_oracle_verify_ragged(_ptr(target), _ptr(draft), _ptr(tokens), _ptr(row_offsets),
-                                       _dtype_code(target), B, V, _ptr(T), _ptr(beta), int(seed),
+                                       _dtype_code(target), B, V, _ptr(T), _ptr(beta), int(uncertainty), int(seed),
                                        _ptr(seq_ids), _ptr(acc), _ptr(out), _ptr(diag), _ptr(path),
                                        _ptr(samp), int(nthreads))
     return OracleResult(acc, out, diag, path, samp, int(rc))

@@ -412,3 +412,65 @@ def test_residual_law_and_empty_residual_fallback(oracle):
     obs2 = np.bincount(r2.tokens[rej2, 0], minlength=V)
     assert obs2[3] == 0
     assert stats.chisquare(np.delete(obs2, 3), np.delete(pt, 3) * rej2.sum()).pvalue > 1e-4
+
+
+# ----------------------------------------------- alternative uncertainty measure (Section 5)
+def test_entropy_against_library(oracle):
+    rng = np.random.default_rng(50)
+    for V in (2, 17, 5000):
+        p = rng.dirichlet(np.ones(V) * 0.3)
+        p[rng.integers(0, V)] = 0.0
+        p /= p.sum()
+        assert oracle.entropy(p) == pytest.approx(stats.entropy(p), rel=1e-12)
+    assert oracle.entropy(np.full(64, 1 / 64)) == pytest.approx(math.log(64), rel=1e-14)
+    assert oracle.entropy(np.array([0.0, 1.0, 0.0])) == 0.0
+
+
+def test_entropy_uncertainty_hand_worked(oracle):
+    # P_t = (1/2, 1/4, 1/8, 1/8): H = 1.75 log 2, log V = 2 log 2 -> uncertainty 7/8 (1 - max P_t
+    # would be 1/2).  P_d uniform, x = 2: R = 1/2.  With beta = 0.4 the tolerance is 0.35:
+    # U <= 0.5 primary, 0.5 < U <= 0.85 pardon, else reject; the max-prob measure would stop at 0.7.
+    T, beta, seed = 1.0, 0.4, 123
+    lt = logits_from_probs([0.5, 0.25, 0.125, 0.125], T)
+    ld = logits_from_probs([0.25] * 4, T)
+    target, draft = np.stack([lt, lt])[None], ld[None, None]
+    tokens = np.array([[2]], dtype=np.int32)
+    for lo, hi, want in [(0.0, 0.45, 1), (0.55, 0.65, 2), (0.72, 0.83, 2), (0.87, 1.0, 0)]:
+        s = _find_seq(oracle, seed, 0, lo, hi)
+        r = oracle.verify(target, draft, tokens, T, beta, seed, seq_ids=np.array([s]),
+                          uncertainty=oracle.UNC_ENTROPY)
+        assert r.d("unc")[0, 0] == pytest.approx(0.875, rel=1e-6)
+        U = r.d("U")[0, 0]
+        assert r.d("thr")[0, 0] == pytest.approx(max(U - 0.35, 0.0), abs=1e-6)
+        assert r.path[0, 0] == want
+    s = _find_seq(oracle, seed, 0, 0.72, 0.83)
+    r = oracle.verify(target, draft, tokens, T, beta, seed, seq_ids=np.array([s]))
+    assert r.path[0, 0] == 0 and r.d("unc")[0, 0] == pytest.approx(0.5, rel=1e-6)
+
+
+def test_entropy_uncertainty_limits_and_acceptance_rate(oracle):
+    rng = np.random.default_rng(51)
+    V, N, T, beta = 8, 20000, 0.8, 0.6
+    # uniform target: uncertainty exactly 1; near one-hot target: close to 0
+    flat = np.zeros(V, dtype=np.float32)
+    peaked = np.array([40.0] + [0.0] * (V - 1), dtype=np.float32)
+    for row, want in ((flat, 1.0), (peaked, 0.0)):
+        r = oracle.verify(np.stack([row, row])[None], row[None, None], np.array([[1]], dtype=np.int32),
+                          T, beta, 1, uncertainty=oracle.UNC_ENTROPY)
+        assert r.d("unc")[0, 0] == pytest.approx(want, abs=1e-12)
+    # acceptance probability min(1, R + beta H / log V) for a fixed token
+    lt = (rng.standard_normal(V) * 1.5).astype(np.float32)
+    ld = (lt + rng.standard_normal(V)).astype(np.float32)
+    pt, pd = softmax64(lt, T), softmax64(ld, T)
+    tol = beta * stats.entropy(pt) / math.log(V)
+    target = np.ascontiguousarray(np.broadcast_to(lt, (N, 2, V)))
+    draft = np.ascontiguousarray(np.broadcast_to(ld, (N, 1, V)))
+    x = int(np.argmin(pt / pd))
+    r = oracle.verify(target, draft, np.full((N, 1), x, dtype=np.int32), T, beta, 77, nthreads=4,
+                      uncertainty=oracle.UNC_ENTROPY)
+    want = min(1.0, pt[x] / pd[x] + tol)
+    assert want < 1.0
+    assert stats.binomtest(int((r.accept_len == 1).sum()), N, want).pvalue > 1e-4
+    # and it differs from the max-prob tolerance
+    want_mp = min(1.0, pt[x] / pd[x] + beta * (1.0 - pt.max()))
+    assert stats.binomtest(int((r.accept_len == 1).sum()), N, want_mp).pvalue < 1e-6
