@@ -50,7 +50,8 @@ typedef enum ears_status {
   EARS_OK = 0,
   EARS_ERR_NULL = 1,      /* a required pointer is NULL */
   EARS_ERR_SHAPE = 2,     /* B, K, V or total_draft_rows out of range */
-  EARS_ERR_PARAM = 3,     /* temperature not finite or <= 0; beta not finite or < 0; bad stages */
+  EARS_ERR_PARAM = 3,     /* temperature not finite or <= 0; beta not finite or < 0; bad stages
+                             or uncertainty measure */
   EARS_ERR_ALIGN = 4,     /* a pointer is not aligned as documented */
   EARS_ERR_DTYPE = 5,     /* dtype is neither EARS_F32 nor EARS_BF16 */
   EARS_ERR_WORKSPACE = 6, /* workspace NULL or smaller than ears_workspace_bytes() */
@@ -72,8 +73,18 @@ enum {
   EARS_STAGE_ALL = 7
 };
 
+/* Uncertainty measure that scales the tolerance.  MAXPROB is the paper's 1 - max_v p_t(v)
+ * (Section 3.2).  ENTROPY is the normalised Shannon entropy H(p_t) / log V of the same
+ * distribution, one of the "more refined uncertainty measures" the paper's Section 5 names; it
+ * comes out of the same single pass over the row. */
+typedef enum ears_uncertainty {
+  EARS_UNCERTAINTY_MAXPROB = 0,
+  EARS_UNCERTAINTY_ENTROPY = 1
+} ears_uncertainty;
+
 /* Number of doubles per (sequence, position) in `out_stats`:
- *   0 m_t  1 Z_t  2 p_t(x)  3 m_d  4 Z_d  5 p_d(x)  6 unc  7 R  8 U  9 thr          */
+ *   0 m_t  1 Z_t  2 p_t(x)  3 m_d  4 Z_d  5 p_d(x)  6 unc  7 R  8 U  9 thr
+ * (unc is the selected uncertainty measure)                                          */
 #define EARS_NSTATS 10
 
 /* Human-readable name of a status code (host pointer to a static string). */
@@ -139,6 +150,9 @@ size_t ears_workspace_bytes(int64_t total_draft_rows, int B, int V);
  *   row_offsets      NULL for a rectangular batch (then K is used and total_draft_rows must be
  *                    B*K); otherwise the CSR offsets of a ragged batch (then K is ignored)
  *   temperature_per_seq, beta_per_seq   device [B] or NULL; when NULL the scalar is used
+ *   uncertainty      an ears_uncertainty; the simple entry points use EARS_UNCERTAINTY_MAXPROB.
+ *                    The statistics stage caches what the selected measure needs, so STATS and
+ *                    DECIDE must be called with the same value
  *   seq_ids          device [B] int64 or NULL: RNG id of each sequence (low 56 bits used);
  *                    NULL means 0..B-1.  With explicit ids a sequence's result does not depend
  *                    on its slot in the batch.
@@ -156,8 +170,8 @@ size_t ears_workspace_bytes(int64_t total_draft_rows, int B, int V);
 int ears_verify_ex(int dtype, const void* target_logits, const void* draft_logits,
                    const int32_t* draft_tokens, const int64_t* row_offsets,
                    int64_t total_draft_rows, int B, int K, int V, float temperature, float beta,
-                   const float* temperature_per_seq, const float* beta_per_seq, uint64_t seed,
-                   const int64_t* seq_ids, void* workspace, size_t workspace_bytes, int stages,
+                   const float* temperature_per_seq, const float* beta_per_seq, int uncertainty,
+                   uint64_t seed, const int64_t* seq_ids, void* workspace, size_t workspace_bytes, int stages,
                    int32_t* out_accept_len, int32_t* out_tokens, double* out_stats,
                    int32_t* out_path, uint32_t* status_word, void* stream);
 

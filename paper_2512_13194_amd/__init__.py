@@ -13,6 +13,8 @@ from .binding import (  # noqa: F401
     EARS_STAGE_DECIDE,
     EARS_STAGE_SAMPLE,
     EARS_STAGE_STATS,
+    EARS_UNCERTAINTY_ENTROPY,
+    EARS_UNCERTAINTY_MAXPROB,
     STAT_NAMES,
     EarsError,
     ears_bench_copy,

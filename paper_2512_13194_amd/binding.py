@@ -20,6 +20,7 @@ EARS_ERR_NULL, EARS_ERR_SHAPE, EARS_ERR_PARAM, EARS_ERR_ALIGN = 1, 2, 3, 4
 EARS_ERR_DTYPE, EARS_ERR_WORKSPACE, EARS_ERR_HIP = 5, 6, 7
 EARS_F32, EARS_BF16 = 0, 1
 EARS_STAGE_STATS, EARS_STAGE_DECIDE, EARS_STAGE_SAMPLE, EARS_STAGE_ALL = 1, 2, 4, 7
+EARS_UNCERTAINTY_MAXPROB, EARS_UNCERTAINTY_ENTROPY = 0, 1
 EARS_NSTATS = 10
 STAT_NAMES = ("m_t", "Z_t", "P_t_x", "m_d", "Z_d", "P_d_x", "unc", "R", "U", "thr")
 
@@ -55,8 +56,8 @@ def lib() -> ctypes.CDLL:
             getattr(L, name).restype = i32
         L.ears_workspace_bytes.argtypes = [i64, i32, i32]
         L.ears_workspace_bytes.restype = sz
-        L.ears_verify_ex.argtypes = [i32, vp, vp, vp, vp, i64, i32, i32, i32, f32, f32, vp, vp, u64,
-                                     vp, vp, sz, i32, vp, vp, vp, vp, vp, vp]
+        L.ears_verify_ex.argtypes = [i32, vp, vp, vp, vp, i64, i32, i32, i32, f32, f32, vp, vp, i32,
+                                     u64, vp, vp, sz, i32, vp, vp, vp, vp, vp, vp]
         L.ears_verify_ex.restype = i32
         L.ears_release.argtypes = []
         L.ears_release.restype = None
@@ -175,7 +176,8 @@ def ears_verify_ragged_bf16(target_logits, draft_logits, draft_tokens, row_offse
 
 
 def ears_verify_ex(target_logits, draft_logits, draft_tokens, *, row_offsets=None, K=None,
-                   temperature=1.0, beta=0.0, temperature_per_seq=None, beta_per_seq=None, seed=0,
+                   temperature=1.0, beta=0.0, temperature_per_seq=None, beta_per_seq=None,
+                   uncertainty=EARS_UNCERTAINTY_MAXPROB, seed=0,
                    seq_ids=None, workspace=None, stages=EARS_STAGE_ALL, out_accept_len=None,
                    out_tokens=None, want_stats=False, want_path=False, status_word=None,
                    stream=None):
@@ -207,7 +209,8 @@ def ears_verify_ex(target_logits, draft_logits, draft_tokens, *, row_offsets=Non
     _check(lib().ears_verify_ex(
         _dtype_code(target_logits), _ptr(target_logits), _ptr(draft_logits), _ptr(draft_tokens),
         _ptr(row_offsets), R, B, K, V, float(temperature), float(beta), _ptr(temperature_per_seq),
-        _ptr(beta_per_seq), int(seed), _ptr(seq_ids), _ptr(workspace), workspace.numel(),
+        _ptr(beta_per_seq), int(uncertainty), int(seed), _ptr(seq_ids), _ptr(workspace),
+        workspace.numel(),
         int(stages), _ptr(out_accept_len), _ptr(out_tokens), _ptr(stats), _ptr(path),
         _ptr(status_word), _stream(stream)))
     return dict(accept_len=out_accept_len, tokens=out_tokens, stats=stats, path=path,

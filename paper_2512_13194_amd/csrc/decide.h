@@ -8,7 +8,8 @@
 namespace ears {
 
 // Decision for draft position i of sequence b (packed row r) from the row statistics: row maximum
-// m, Z = sum exp((l-m)/T) and the draft token's logit lx, for the target (t) and draft (d) rows.
+// m, Z = sum exp((l-m)/T) and the draft token's logit lx, for the target (t) and draft (d) rows,
+// and the target row's uncertainty unc (1 - 1/Z_t = 1 - max P_t, or the entropy measure).
 // Evaluated in fp64 whenever fp32 could not tell, so the outcome does not depend on fp32 rounding
 // of R or the threshold.  Returns 0 reject, 1 accepted by R >= U, 2 accepted only through the
 // tolerance (1 for either kind of acceptance when neither statistics nor branch ids are asked
@@ -16,7 +17,7 @@ namespace ears {
 // an invalid token.
 __device__ __forceinline__ int decide_position(const Problem& p, int b, int i, int64_t r, double mt,
                                                double Zt, double lxt, double md, double Zd,
-                                               double lxd) {
+                                               double lxd, double unc) {
   const double T = (double)seq_temperature(p, b);
   const double beta = (double)seq_beta(p, b);
   const int32_t x = p.tokens[r];
@@ -31,7 +32,7 @@ __device__ __forceinline__ int decide_position(const Problem& p, int b, int i, i
     if (Pdf > 1e-9f) {
       const float Rf = Ptf / Pdf;
       const float Uf = (float)accept_uniform(p.seed, seq_rng_id(p, b), (uint32_t)i);
-      const float thrf = fmaxf(Uf - (float)beta * (1.0f - 1.0f / (float)Zt), 0.0f);
+      const float thrf = fmaxf(Uf - (float)beta * (float)unc, 0.0f);
       const float slack = 1e-6f * (1.0f + (float)beta);
       if (Rf * (1.0f - 1e-4f) > thrf + slack) return 1;
       if (Rf * (1.0f + 1e-4f) < thrf - slack) return 0;
@@ -41,7 +42,6 @@ __device__ __forceinline__ int decide_position(const Problem& p, int b, int i, i
   const double Pdx = valid ? exp((lxd - md) / T) / Zd : 0.0;
   const double R = Ptx / fmax(Pdx, kEpsilon);                              // step 2, division guard
   const double U = accept_uniform(p.seed, seq_rng_id(p, b), (uint32_t)i);  // step 3
-  const double unc = 1.0 - 1.0 / Zt;                      // 1 - max P_t; max P_t = 1/Z_t
   const double tol = beta * unc;                          // step 4
   const double thr = fmax(U - tol, 0.0);                  // threshold clamp
   int decision;                                           // step 5
@@ -79,8 +79,11 @@ __device__ __forceinline__ int first_reject_scan(const Problem& p, int b, int la
       if (from_memory) {
         decision = p.decisions[r];
       } else {
-        decision = decide_position(p, b, i, r, (double)p.m[2 * r], p.Z[2 * r], (double)p.lx[2 * r],
-                                   (double)p.m[2 * r + 1], p.Z[2 * r + 1], (double)p.lx[2 * r + 1]);
+        const double Zt = p.Z[2 * r];
+        const double unc = p.unc_mode ? p.unc[r] : 1.0 - 1.0 / Zt;  // max P_t = 1/Z_t
+        decision = decide_position(p, b, i, r, (double)p.m[2 * r], Zt, (double)p.lx[2 * r],
+                                   (double)p.m[2 * r + 1], p.Z[2 * r + 1], (double)p.lx[2 * r + 1],
+                                   unc);
         p.decisions[r] = decision;
       }
     }

@@ -34,7 +34,7 @@ namespace ears {
 // Host side.
 // =================================================================================================
 struct WorkspaceLayout {
-  size_t off_Z, off_m, off_lx, off_decisions, off_records, total;
+  size_t off_Z, off_m, off_lx, off_unc, off_decisions, off_records, total;
   int S, chunk;  // how the sampling stage splits a row
 };
 
@@ -65,6 +65,7 @@ static bool workspace_layout(int64_t R, int B, int V, WorkspaceLayout* w) {
   w->off_Z = o;        o = align_up(o + (size_t)(2 * R) * sizeof(double), 256);
   w->off_m = o;        o = align_up(o + (size_t)(2 * R) * sizeof(float), 256);
   w->off_lx = o;       o = align_up(o + (size_t)(2 * R) * sizeof(float), 256);
+  w->off_unc = o;      o = align_up(o + (size_t)R * sizeof(double), 256);
   w->off_decisions = o; o = align_up(o + (size_t)R * sizeof(int32_t), 256);
   w->off_records = o;  o = align_up(o + (size_t)B * S4 * kRecordWords * sizeof(uint32_t), 256);
   w->total = o;
@@ -112,10 +113,15 @@ static int launch(Problem p, int stages, hipStream_t stream) {
   const bool fused = stats && decide && sample;
   p.decide_fused = fused ? 1 : 0;
   if (stats) {
-    if (fused)
-      hipLaunchKernelGGL((row_stats_kernel<DT, 4, true>), dim3((unsigned)p.R), dim3(kBlock), 0, stream, p);
+    const dim3 grid((unsigned)p.R), block(kBlock);
+    if (fused && p.unc_mode)
+      hipLaunchKernelGGL((row_stats_kernel<DT, 4, true, true>), grid, block, 0, stream, p);
+    else if (fused)
+      hipLaunchKernelGGL((row_stats_kernel<DT, 4, true, false>), grid, block, 0, stream, p);
+    else if (p.unc_mode)
+      hipLaunchKernelGGL((row_stats_kernel<DT, 4, false, true>), grid, block, 0, stream, p);
     else
-      hipLaunchKernelGGL((row_stats_kernel<DT, 4, false>), dim3((unsigned)p.R), dim3(kBlock), 0, stream, p);
+      hipLaunchKernelGGL((row_stats_kernel<DT, 4, false, false>), grid, block, 0, stream, p);
   }
   if (decide && !fused) {
     hipLaunchKernelGGL(decide_kernel, dim3((unsigned)((p.B + kWavesPerBlock - 1) / kWavesPerBlock)),
@@ -182,8 +188,9 @@ size_t ears_workspace_bytes(int64_t total_draft_rows, int B, int V) {
 int ears_verify_ex(int dtype, const void* target_logits, const void* draft_logits,
                    const int32_t* draft_tokens, const int64_t* row_offsets,
                    int64_t total_draft_rows, int B, int K, int V, float temperature, float beta,
-                   const float* temperature_per_seq, const float* beta_per_seq, uint64_t seed,
-                   const int64_t* seq_ids, void* workspace, size_t workspace_bytes, int stages,
+                   const float* temperature_per_seq, const float* beta_per_seq, int uncertainty,
+                   uint64_t seed, const int64_t* seq_ids, void* workspace, size_t workspace_bytes,
+                   int stages,
                    int32_t* out_accept_len, int32_t* out_tokens, double* out_stats,
                    int32_t* out_path, uint32_t* status_word, void* stream) {
   WorkspaceLayout lay;
@@ -192,6 +199,8 @@ int ears_verify_ex(int dtype, const void* target_logits, const void* draft_logit
                           beta_per_seq, seq_ids, workspace, workspace_bytes, stages, out_accept_len,
                           out_tokens, out_stats, out_path, status_word, &lay);
   if (rc != EARS_OK) return rc;
+  if (uncertainty != EARS_UNCERTAINTY_MAXPROB && uncertainty != EARS_UNCERTAINTY_ENTROPY)
+    return EARS_ERR_PARAM;
   Problem p;
   p.target = target_logits;
   p.draft = draft_logits;
@@ -211,6 +220,8 @@ int ears_verify_ex(int dtype, const void* target_logits, const void* draft_logit
   p.Z = reinterpret_cast<double*>(ws + lay.off_Z);
   p.m = reinterpret_cast<float*>(ws + lay.off_m);
   p.lx = reinterpret_cast<float*>(ws + lay.off_lx);
+  p.unc = reinterpret_cast<double*>(ws + lay.off_unc);
+  p.unc_mode = uncertainty;
   p.decisions = reinterpret_cast<int32_t*>(ws + lay.off_decisions);
   p.records = reinterpret_cast<uint32_t*>(ws + lay.off_records);
   p.S = 0;
@@ -240,7 +251,8 @@ static int verify_simple(int dtype, const void* target, const void* draft, const
   rc = scratch_get(lay.total, &ws);
   if (rc != EARS_OK) return rc;
   return ears_verify_ex(dtype, target, draft, tokens, row_offsets, R, B, K, V, T, beta, T_seq,
-                        beta_seq, seed, nullptr, ws, lay.total, EARS_STAGE_ALL, out_accept_len,
+                        beta_seq, EARS_UNCERTAINTY_MAXPROB, seed, nullptr, ws, lay.total,
+                        EARS_STAGE_ALL, out_accept_len,
                         out_tokens, nullptr, nullptr, nullptr, stream);
 }
 

@@ -22,30 +22,53 @@ namespace ears {
 // only the fp32 rounding of the individual terms.  max P = 1/Z needs no second pass
 // (Section 3.3 item 1: the maximum is cached, the row is never re-scanned for it).
 // =================================================================================================
-template <int N>
+//
+// With kEntropy the lane also keeps W = sum e*y over the same terms, e = exp2(y),
+// y = l*c - fl(m*c) (clamped at -126 so that a masked entry contributes 0 * finite), which
+// rescales as W <- f*(W + d*S) when the offset moves by d (f = 2^d).  The Shannon entropy of the
+// row is then H = ln Z - ln 2 * W/S, one more FMA and one max per element.
+template <int N, bool kEntropy>
 __device__ __forceinline__ void accumulate(const float (&f)[N], float c, float& m_run, float& mc,
-                                           float& S) {
+                                           float& S, float& W) {
   float cm = f[0];
 #pragma unroll
   for (int j = 1; j < N; ++j) cm = fmaxf(cm, f[j]);
   if (cm > m_run) {
     const float mc_new = cm * c;
-    S = (m_run == -INFINITY) ? 0.0f : S * __builtin_amdgcn_exp2f(mc - mc_new);
+    if (m_run == -INFINITY) {
+      S = 0.0f;
+      W = 0.0f;
+    } else {
+      const float d = mc - mc_new;
+      const float scale = __builtin_amdgcn_exp2f(d);
+      if (kEntropy) W = scale * fmaf(d, S, W);
+      S *= scale;
+    }
     m_run = cm;
     mc = mc_new;
   }
   float s[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+  float w[4] = {0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
-  for (int j = 0; j < N; ++j) s[j & 3] += __builtin_amdgcn_exp2f(fmaf(f[j], c, -mc));
+  for (int j = 0; j < N; ++j) {
+    float y = fmaf(f[j], c, -mc);
+    if (kEntropy) y = fmaxf(y, -126.0f);
+    const float e = __builtin_amdgcn_exp2f(y);
+    s[j & 3] += e;
+    if (kEntropy) w[j & 3] = fmaf(e, y, w[j & 3]);
+  }
   S += (s[0] + s[1]) + (s[2] + s[3]);
+  if (kEntropy) W += (w[0] + w[1]) + (w[2] + w[3]);
 }
 
-// Streams one row; on return thread 0 holds the row maximum M and Z = sum exp((l - M)/T).
-template <typename DT, int kUnroll>
+// Streams one row; on return thread 0 holds the row maximum M, Z = sum exp((l - M)/T) and, with
+// kEntropy, the Shannon entropy H (nats) of softmax(l/T).
+template <typename DT, int kUnroll, bool kEntropy>
 __device__ __forceinline__ void row_pass(const typename DT::storage* base, int V, float c,
-                                         float* sh_m, double* sh_s, float& M_out, double& Z_out) {
+                                         float* sh_m, double* sh_s, float& M_out, double& Z_out,
+                                         double& H_out) {
   const int tid = (int)threadIdx.x;
-  float m_run = -INFINITY, mc = 0.0f, S = 0.0f;
+  float m_run = -INFINITY, mc = 0.0f, S = 0.0f, W = 0.0f;
 
   // scalar head up to the first 16-byte boundary and scalar tail after the last whole vector
   // (both empty when rows are 16-byte multiples)
@@ -58,7 +81,7 @@ __device__ __forceinline__ void row_pass(const typename DT::storage* base, int V
   const int ntail = V - tail0;
   if (tid < head + ntail) {
     float f[1] = {DT::load(base, tid < head ? tid : tail0 + (tid - head))};
-    accumulate<1>(f, c, m_run, mc, S);
+    accumulate<1, kEntropy>(f, c, m_run, mc, S, W);
   }
 
   const uint4* vp = reinterpret_cast<const uint4*>(base + head);
@@ -77,7 +100,7 @@ __device__ __forceinline__ void row_pass(const typename DT::storage* base, int V
 #pragma unroll
       for (int j = 0; j < kPer; ++j) f[u * kPer + j] = g[j];
     }
-    accumulate<kUnroll * kPer>(f, c, m_run, mc, S);
+    accumulate<kUnroll * kPer, kEntropy>(f, c, m_run, mc, S, W);
   }
 
   // merge the lanes of the workgroup
@@ -92,23 +115,36 @@ __device__ __forceinline__ void row_pass(const typename DT::storage* base, int V
   const float Mc = M * c;
   const float scale = (m_run == -INFINITY) ? 0.0f : __builtin_amdgcn_exp2f(mc - Mc);
   const double part = wave_sum((double)S * (double)scale);
-  if (lane == 0) sh_s[wave] = part;
+  double wpart = 0.0;
+  if (kEntropy) wpart = wave_sum((double)scale * ((double)W + (double)(mc - Mc) * (double)S));
+  if (lane == 0) {
+    sh_s[wave] = part;
+    if (kEntropy) sh_s[kWavesPerBlock + wave] = wpart;
+  }
   __syncthreads();
   if (tid == 0) {
-    double Zp = 0.0;
+    double Zp = 0.0, Wp = 0.0;
 #pragma unroll
     for (int w = 0; w < kWavesPerBlock; ++w) Zp += sh_s[w];
     // the lanes used fl(M*c) as the offset; undo its rounding exactly
-    Z_out = Zp * exp2((double)Mc - (double)M * (double)c);
+    const double delta = (double)Mc - (double)M * (double)c;
+    Z_out = Zp * exp2(delta);
     M_out = M;
+    if (kEntropy) {
+#pragma unroll
+      for (int w = 0; w < kWavesPerBlock; ++w) Wp += sh_s[kWavesPerBlock + w];
+      // H = ln Z - ln 2 * sum p*y2; the offset's rounding shifts both terms equally, so the
+      // sums taken with fl(M*c) serve as they are
+      H_out = log(Zp) - 0.69314718055994530942 * (Wp / Zp);
+    }
   }
 }
 
-template <typename DT, int kUnroll, bool kDecide>
+template <typename DT, int kUnroll, bool kDecide, bool kEntropy>
 __global__ __launch_bounds__(kBlock) void row_stats_kernel(Problem p) {
   using storage = typename DT::storage;
   __shared__ float sh_m[kWavesPerBlock];
-  __shared__ double sh_s[kWavesPerBlock];
+  __shared__ double sh_s[2 * kWavesPerBlock];
   const int64_t r = (int64_t)blockIdx.x;
   const int b = seq_of_row(p, r);
   const int V = p.V;
@@ -127,9 +163,9 @@ __global__ __launch_bounds__(kBlock) void row_stats_kernel(Problem p) {
   }
 
   float Mt = 0.0f, Md = 0.0f;
-  double Zt = 0.0, Zd = 0.0;
-  row_pass<DT, kUnroll>(trow, V, c, sh_m, sh_s, Mt, Zt);
-  row_pass<DT, kUnroll>(drow, V, c, sh_m, sh_s, Md, Zd);
+  double Zt = 0.0, Zd = 0.0, Ht = 0.0, Hd = 0.0;
+  row_pass<DT, kUnroll, kEntropy>(trow, V, c, sh_m, sh_s, Mt, Zt, Ht);
+  row_pass<DT, kUnroll, false>(drow, V, c, sh_m, sh_s, Md, Zd, Hd);
 
   if (threadIdx.x == 0) {
     p.Z[2 * r] = Zt;
@@ -138,10 +174,16 @@ __global__ __launch_bounds__(kBlock) void row_stats_kernel(Problem p) {
     p.m[2 * r + 1] = Md;
     p.lx[2 * r] = lxt;
     p.lx[2 * r + 1] = lxd;
+    // uncertainty of the target distribution: 1 - max P_t = 1 - 1/Z_t, or H / log V
+    double unc = 1.0 - 1.0 / Zt;
+    if (kEntropy) {
+      unc = V > 1 ? fmin(fmax(Ht / log((double)V), 0.0), 1.0) : 0.0;
+      p.unc[r] = unc;
+    }
     if (kDecide) {
       const int i = (int)(r - seq_row_begin(p, b));
       p.decisions[r] = decide_position(p, b, i, r, (double)Mt, Zt, (double)lxt, (double)Md, Zd,
-                                       (double)lxd);
+                                       (double)lxd, unc);
     }
   }
 }

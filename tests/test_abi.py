@@ -77,10 +77,10 @@ def test_rect_argument_errors(L):
 
 
 def _ex(L, dtype=1, target=P, draft=P, tokens=P, off=None, R=6, B=2, K=3, V=64, T=1.0, beta=0.1,
-        Ts=None, betas=None, seed=0, ids=None, ws=P, wsb=1 << 20, stages=7, acc=P, out=P,
+        Ts=None, betas=None, unc=0, seed=0, ids=None, ws=P, wsb=1 << 20, stages=7, acc=P, out=P,
         stats=None, path=None, status=None):
-    return L.ears_verify_ex(dtype, target, draft, tokens, off, R, B, K, V, T, beta, Ts, betas, seed,
-                            ids, ws, wsb, stages, acc, out, stats, path, status, None)
+    return L.ears_verify_ex(dtype, target, draft, tokens, off, R, B, K, V, T, beta, Ts, betas, unc,
+                            seed, ids, ws, wsb, stages, acc, out, stats, path, status, None)
 
 
 def test_ex_argument_errors(L):
@@ -91,6 +91,8 @@ def test_ex_argument_errors(L):
     assert _ex(L, off=P, R=1, B=2) == b.EARS_ERR_SHAPE     # ragged: at least one row per sequence
     assert _ex(L, stages=0) == b.EARS_ERR_PARAM
     assert _ex(L, stages=8) == b.EARS_ERR_PARAM
+    assert _ex(L, unc=2) == b.EARS_ERR_PARAM
+    assert _ex(L, unc=-1) == b.EARS_ERR_PARAM
     assert _ex(L, T=0.0) == b.EARS_ERR_PARAM
     assert _ex(L, T=0.0, Ts=P, ws=None) == b.EARS_ERR_WORKSPACE   # per-sequence T: scalar ignored
     assert _ex(L, ws=None) == b.EARS_ERR_WORKSPACE

@@ -26,21 +26,23 @@ def _log(msg):
     print(msg, flush=True)
 
 
-def run_rect(ears, oracle, batch, T, beta, seed, seq_ids=None, check_simple=True):
+def run_rect(ears, oracle, batch, T, beta, seed, seq_ids=None, check_simple=True, uncertainty=0):
     from paper_2512_13194_amd import inputs
     B, K, V = batch.B, batch.K, batch.V
     ids_dev = None if seq_ids is None else torch.as_tensor(seq_ids, dtype=torch.int64, device="cuda")
     out = ears.ears_verify_ex(batch.target, batch.draft, batch.tokens, temperature=T, beta=beta,
-                              seed=seed, seq_ids=ids_dev, want_stats=True, want_path=True)
+                              seed=seed, seq_ids=ids_dev, want_stats=True, want_path=True,
+                              uncertainty=uncertainty)
     torch.cuda.synchronize()
     # the ABI takes temperature and beta as float32: the oracle gets exactly those values
     ora = oracle.verify(inputs.logits_to_numpy(batch.target), inputs.logits_to_numpy(batch.draft),
                         batch.tokens.cpu().numpy(), float(np.float32(T)), float(np.float32(beta)),
-                        seed, seq_ids=seq_ids, nthreads=NTHREADS)
+                        seed, seq_ids=seq_ids, nthreads=NTHREADS, uncertainty=uncertainty)
     rep = compare(ora, out["accept_len"].cpu().numpy(), out["tokens"].cpu().numpy(),
                   out["stats"].cpu().numpy(), out["path"].cpu().numpy(), None, K,
-                  RTOL[batch.target.dtype], batch.tokens.cpu().numpy(), V)
-    if check_simple and seq_ids is None:
+                  RTOL[batch.target.dtype], batch.tokens.cpu().numpy(), V,
+                  unc_is_maxprob=(uncertainty == 0))
+    if check_simple and seq_ids is None and uncertainty == 0:
         fn = ears.ears_verify_f32 if batch.target.dtype == torch.float32 else ears.ears_verify_bf16
         acc, tok = fn(batch.target, batch.draft, batch.tokens, T, beta, seed)
         torch.cuda.synchronize()
@@ -49,19 +51,23 @@ def run_rect(ears, oracle, batch, T, beta, seed, seq_ids=None, check_simple=True
     return rep, ora, out
 
 
-def run_ragged(ears, oracle, batch, seed):
+def run_ragged(ears, oracle, batch, seed, uncertainty=0):
     from paper_2512_13194_amd import inputs
     out = ears.ears_verify_ex(batch.target, batch.draft, batch.tokens, row_offsets=batch.row_offsets,
                               temperature_per_seq=batch.temperature, beta_per_seq=batch.beta,
-                              seed=seed, want_stats=True, want_path=True)
+                              seed=seed, want_stats=True, want_path=True, uncertainty=uncertainty)
     torch.cuda.synchronize()
     off = batch.row_offsets.cpu().numpy()
     ora = oracle.verify_ragged(inputs.logits_to_numpy(batch.target), inputs.logits_to_numpy(batch.draft),
                                batch.tokens.cpu().numpy(), off, batch.temperature.cpu().numpy(),
-                               batch.beta.cpu().numpy(), seed, nthreads=NTHREADS)
+                               batch.beta.cpu().numpy(), seed, nthreads=NTHREADS,
+                               uncertainty=uncertainty)
     rep = compare(ora, out["accept_len"].cpu().numpy(), out["tokens"].cpu().numpy(),
                   out["stats"].cpu().numpy(), out["path"].cpu().numpy(), off, None,
-                  RTOL[batch.target.dtype], batch.tokens.cpu().numpy(), batch.V)
+                  RTOL[batch.target.dtype], batch.tokens.cpu().numpy(), batch.V,
+                  unc_is_maxprob=(uncertainty == 0))
+    if uncertainty != 0:
+        return rep, ora, out
     fn = ears.ears_verify_ragged_f32 if batch.target.dtype == torch.float32 else ears.ears_verify_ragged_bf16
     acc, tok = fn(batch.target, batch.draft, batch.tokens, batch.row_offsets, batch.temperature,
                   batch.beta, seed)
@@ -212,6 +218,70 @@ def test_stages_split_reuses_cached_statistics(ears, oracle):
     acc = full["accept_len"].cpu().numpy()
     t = n_only.view(12, 4).cpu().numpy()
     assert all(t[i, acc[i]] == -1 for i in range(12))
+
+
+# ------------------------------------------------- entropy-based uncertainty (Section 5 outlook)
+@pytest.mark.parametrize("index", [0, 2])
+def test_entropy_uncertainty_workloads(ears, oracle, index):
+    from paper_2512_13194_amd import inputs
+    cfg = inputs.CONFIGS[index]
+    T = cfg["temperatures"][0]
+    batch = inputs.make_config(index, T=T, device="cuda")
+    for beta in (cfg["betas"][-1], 1.0):
+        _log("entropy workload %s T=%s beta=%s" % (cfg["name"], T, beta))
+        rep, ora, out = run_rect(ears, oracle, batch, T, beta, cfg["seed"],
+                                 uncertainty=ears.EARS_UNCERTAINTY_ENTROPY)
+        _log("  " + rep.line() + " mean_accept=%.3f" % ora.accept_len.mean())
+        assert rep.exempt_decisions <= 1 and rep.exempt_tokens <= 1
+        # the measure changes decisions: the run is not a replay of the max-probability one
+        unc = out["stats"][:, 6].cpu().numpy()
+        assert (unc >= 0).all() and (unc <= 1).all()
+        assert np.abs(unc - (1.0 - 1.0 / out["stats"][:, 1].cpu().numpy())).max() > 1e-3
+
+
+@pytest.mark.parametrize("B,K,V,dtype", [
+    (1, 1, 1, torch.float32), (3, 2, 8, torch.float32), (5, 3, 13, torch.bfloat16),
+    (2, 4, 4099, torch.float32), (7, 8, 8192, torch.bfloat16), (2, 3, 65537, torch.bfloat16),
+])
+def test_entropy_uncertainty_edge_shapes(ears, oracle, B, K, V, dtype):
+    from paper_2512_13194_amd import inputs
+    _log("entropy edge B=%d K=%d V=%d %s" % (B, K, V, dtype))
+    batch = inputs.make_rect(B, K, V, dtype, T=0.7, data_seed=B * 1000 + V + 1, draft_noise=1.0,
+                             device="cuda")
+    rep, _, _ = run_rect(ears, oracle, batch, 0.7, 0.5, 21, uncertainty=ears.EARS_UNCERTAINTY_ENTROPY)
+    assert rep.exempt_decisions == 0 and rep.exempt_tokens == 0
+
+
+def test_entropy_uncertainty_masked_peaked_ragged_and_stages(ears, oracle):
+    from paper_2512_13194_amd import inputs
+    ENT = ears.EARS_UNCERTAINTY_ENTROPY
+    _log("entropy masked / peaked")
+    batch = inputs.make_rect(16, 4, 5000, torch.bfloat16, T=1.0, data_seed=78, draft_noise=1.0,
+                             peaked_frac=0.3, peaked_sigma=12.0, device="cuda")
+    mask = torch.rand(5000, device="cuda") < 0.4
+    batch.target[:, :, mask] = float("-inf")
+    batch.draft[:, :, mask] = float("-inf")
+    # one target row with a single unmasked entry: entropy exactly 0
+    batch.target[1, 0, :] = float("-inf")
+    batch.target[1, 0, 17] = 3.0
+    rep, ora, out = run_rect(ears, oracle, batch, 1.0, 0.6, 10, uncertainty=ENT)
+    assert rep.exempt_decisions == 0 and rep.exempt_tokens == 0
+    # fp32 rounding of the single exp2 term bounds what the kernel can resolve
+    assert abs(out["stats"][1 * 4 + 0, 6].item()) < 1e-7 and ora.diag[1, 0, 6] == 0.0
+
+    _log("entropy ragged")
+    rb = inputs.make_ragged(37, 3001, torch.bfloat16, data_seed=83, device="cuda")
+    rep, _, _ = run_ragged(ears, oracle, rb, 15, uncertainty=ENT)
+    assert rep.exempt_decisions == 0 and rep.exempt_tokens == 0
+
+    _log("entropy stages")
+    kw = dict(temperature=1.0, beta=0.6, seed=10, uncertainty=ENT)
+    a = ears.ears_verify_ex(batch.target, batch.draft, batch.tokens, stages=ears.EARS_STAGE_STATS, **kw)
+    b = ears.ears_verify_ex(batch.target, batch.draft, batch.tokens,
+                            stages=ears.EARS_STAGE_DECIDE | ears.EARS_STAGE_SAMPLE,
+                            workspace=a["workspace"], **kw)
+    torch.cuda.synchronize()
+    assert torch.equal(b["accept_len"], out["accept_len"]) and torch.equal(b["tokens"], out["tokens"])
 
 
 def test_ragged_small(ears, oracle):
