@@ -324,7 +324,10 @@ int ears_bench_read(const void* src, size_t bytes, uint32_t* sink, void* stream)
   size_t rounds = (nvec + 1024 * kBenchSlabVecs / 2) / (1024 * kBenchSlabVecs);
   if (rounds < 1) rounds = 1;
   const size_t slab_vecs = (nvec + 1024 * rounds - 1) / (1024 * rounds);
-  hipLaunchKernelGGL(bench_read_kernel, dim3(kBenchBlocks), dim3(kBlock), 0,
+  // two slabs per workgroup, half a buffer apart, like the target and draft rows of one position
+  size_t blocks = 1024 * ((rounds + 1) / 2);
+  if (blocks > (size_t)kBenchBlocks) blocks = kBenchBlocks;
+  hipLaunchKernelGGL(bench_read_kernel, dim3((unsigned)blocks), dim3(kBlock), 0,
                      static_cast<hipStream_t>(stream), static_cast<const uint4*>(src), nvec,
                      slab_vecs, sink);
   return hipGetLastError() == hipSuccess ? EARS_OK : EARS_ERR_HIP;
