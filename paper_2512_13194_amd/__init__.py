@@ -1,6 +1,7 @@
 """EARS verification step for AMD MI355X: Python binding of the HIP library.
 
 `paper_2512_13194_amd.binding` mirrors the C ABI of include/ears.h name for name;
+`paper_2512_13194_amd.sampler` wraps it in a verifier object for a decoding loop;
 `paper_2512_13194_amd.inputs` draws the seeded synthetic workloads;
 `paper_2512_13194_amd.build` compiles libears.so in-tree with hipcc.
 """
@@ -29,3 +30,4 @@ from .binding import (  # noqa: F401
     lib,
     status_string,
 )
+from .sampler import EarsVerifier, VerifyResult, acceptance_sweep  # noqa: F401,E402

@@ -33,12 +33,20 @@ class EarsVerifier:
     temperature / beta are the sampling temperature and the base tolerance of the paper
     (Section 3.2; its experiments use T = 0.9, beta = 0.1).  beta = 0 is standard speculative
     sampling.  `seed` fixes the whole noise stream: step t of sequence id s always sees the same
-    random numbers, whatever slot of the batch the sequence occupies.
+    random numbers, whatever slot of the batch the sequence occupies.  `uncertainty` selects what
+    scales the tolerance: "maxprob" (the paper's 1 - max P_target) or "entropy" (normalised
+    Shannon entropy, the refinement its Section 5 names).
     """
 
+    UNCERTAINTY = {"maxprob": binding.EARS_UNCERTAINTY_MAXPROB,
+                   "entropy": binding.EARS_UNCERTAINTY_ENTROPY}
+
     def __init__(self, temperature: float = 0.9, beta: float = 0.1, seed: int = 0,
-                 telemetry: bool = False):
+                 telemetry: bool = False, uncertainty: str = "maxprob"):
         binding.lib()  # fail now, loudly, if the HIP library has not been built
+        if uncertainty not in self.UNCERTAINTY:
+            raise ValueError("uncertainty must be one of %s" % sorted(self.UNCERTAINTY))
+        self.uncertainty = self.UNCERTAINTY[uncertainty]
         self.temperature = float(temperature)
         self.beta = float(beta)
         self.seed = int(seed) & _MASK64
@@ -87,7 +95,8 @@ class EarsVerifier:
         out = binding.ears_verify_ex(
             target_logits, draft_logits, draft_tokens, row_offsets=row_offsets,
             temperature=self.temperature, beta=self.beta, temperature_per_seq=temperature_per_seq,
-            beta_per_seq=beta_per_seq, seed=self.step_seed(t), seq_ids=seq_ids,
+            beta_per_seq=beta_per_seq, uncertainty=self.uncertainty, seed=self.step_seed(t),
+            seq_ids=seq_ids,
             workspace=self._workspace, out_accept_len=self._acc, out_tokens=self._tok,
             want_stats=want_stats, want_path=self._path if self.telemetry else False)
         if step is None:
@@ -118,12 +127,14 @@ class EarsVerifier:
                 "mean_accept_len": c["accepted_tokens"] / max(c["sequences"], 1)}
 
 
-def acceptance_sweep(batch, betas, temperature: float, seed: int = 0) -> list:
+def acceptance_sweep(batch, betas, temperature: float, seed: int = 0,
+                     uncertainty: str = "maxprob") -> list:
     """Branch rates and mean accepted length of one rectangular batch for each beta (the
     efficiency / quality trade-off of Section 4.3)."""
     rows = []
     for beta in betas:
-        v = EarsVerifier(temperature=temperature, beta=beta, seed=seed, telemetry=True)
+        v = EarsVerifier(temperature=temperature, beta=beta, seed=seed, telemetry=True,
+                         uncertainty=uncertainty)
         v.verify(batch.target, batch.draft, batch.tokens, step=0)
         rows.append(dict(beta=float(beta), temperature=float(temperature), **v.summary()))
     return rows
