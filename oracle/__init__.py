@@ -17,5 +17,6 @@ from .ears_oracle import (  # noqa: F401
     philox4x32_10,
     softmax,
     verify,
+    verify_greedy,
     verify_ragged,
 )

@@ -284,3 +284,44 @@ int ears_oracle_verify_ragged(const void* target, const void* draft, const int32
   }
   return rc;
 }
+
+/* ------------------------------------------------------------------------------------------ */
+/* The deterministic corner, temperature -> 0 (the paper's introduction: the standard scheme at
+ * temperature = 0).  softmax(l / T) tends to the indicator of the row's largest logit, so the
+ * ratio of Section 3.2 step 2 tends to 1 when the draft token is the target row's arg-max and to
+ * 0 otherwise, the uncertainty 1 - max P_t tends to 0 and with it the tolerance, and the residual
+ * and the bonus distribution both tend to the indicator of the target arg-max.  Hence: accept
+ * while the draft token equals arg-max of the target row; the token at the first mismatch (or
+ * after K matches) is that row's arg-max.  Equal maxima: lowest index.  No random numbers. */
+static int32_t argmax_row(const void* row, int dtype, int V) {
+  int32_t best = 0;
+  double bv = logit_at(row, dtype, 0);
+  for (int v = 1; v < V; ++v) {
+    double x = logit_at(row, dtype, v);
+    if (x > bv) {
+      bv = x;
+      best = v;
+    }
+  }
+  return best;
+}
+
+void ears_oracle_verify_greedy(const void* target, const int32_t* tokens,
+                               const int64_t* row_offsets, int dtype, int B, int K, int V,
+                               int32_t* accept_len, int32_t* out_tokens, int32_t* target_argmax) {
+  for (int b = 0; b < B; ++b) {
+    int64_t r0 = row_offsets ? row_offsets[b] : (int64_t)b * K;
+    int Kb = row_offsets ? (int)(row_offsets[b + 1] - r0) : K;
+    int n = Kb;
+    for (int i = 0; i <= Kb; ++i) {
+      int32_t a = argmax_row(row_ptr(target, dtype, r0 + b + i, V), dtype, V);
+      if (target_argmax) target_argmax[r0 + b + i] = a;
+      if (i < Kb && n == Kb && tokens[r0 + i] != a) n = i;
+    }
+    accept_len[b] = n;
+    for (int i = 0; i <= Kb; ++i) {
+      int32_t a = argmax_row(row_ptr(target, dtype, r0 + b + i, V), dtype, V);
+      out_tokens[r0 + b + i] = i < n ? tokens[r0 + i] : (i == n ? a : -1);
+    }
+  }
+}

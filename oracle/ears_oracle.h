@@ -118,6 +118,15 @@ int ears_oracle_verify_ragged(const void* target, const void* draft, const int32
                               int32_t* accept_len, int32_t* out_tokens, double* diag,
                               int32_t* path, double* samp, int nthreads);
 
+/* Temperature -> 0 (greedy) corner: accept while the draft token equals the arg-max of its
+ * target row (lowest index among equal maxima); out_tokens gets the accepted prefix, the target
+ * arg-max of row n, then -1.  Rectangular when row_offsets is NULL (target [B, K+1, V], tokens
+ * [B, K]), otherwise packed like ears_oracle_verify_ragged.  target_argmax (optional) receives the
+ * arg-max of every target row, packed like the target rows. */
+void ears_oracle_verify_greedy(const void* target, const int32_t* tokens,
+                               const int64_t* row_offsets, int dtype, int B, int K, int V,
+                               int32_t* accept_len, int32_t* out_tokens, int32_t* target_argmax);
+
 #ifdef __cplusplus
 }
 #endif

@@ -73,6 +73,9 @@ def _load():
         c.c_void_p, c.c_int, c.c_uint64, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p,
         c.c_void_p, c.c_int]
     lib.ears_oracle_verify_ragged.restype = c.c_int
+    lib.ears_oracle_verify_greedy.argtypes = [c.c_void_p, c.c_void_p, c.c_void_p, c.c_int, c.c_int,
+                                              c.c_int, c.c_int, c.c_void_p, c.c_void_p, c.c_void_p]
+    lib.ears_oracle_verify_greedy.restype = None
     _lib = lib
     return lib
 
@@ -205,3 +208,31 @@ def verify_ragged(target: np.ndarray, draft: np.ndarray, tokens: np.ndarray,
                                        _ptr(seq_ids), _ptr(acc), _ptr(out), _ptr(diag), _ptr(path),
                                        _ptr(samp), int(nthreads))
     return OracleResult(acc, out, diag, path, samp, int(rc))
+
+
+def verify_greedy(target: np.ndarray, tokens: np.ndarray, row_offsets: Optional[np.ndarray] = None):
+    """Temperature -> 0 corner.  Rectangular: target [B, K+1, V], tokens [B, K].  Ragged: target
+    [R + B, V], tokens [R], row_offsets [B+1].  Returns (accept_len, out_tokens, target_argmax)."""
+    lib = _load()
+    target = np.ascontiguousarray(target)
+    tokens = np.ascontiguousarray(tokens, dtype=np.int32)
+    if row_offsets is None:
+        B, K1, V = target.shape
+        K = K1 - 1
+        assert tokens.shape == (B, K)
+        nrows = B * K1
+        shape = (B, K1)
+    else:
+        row_offsets = np.ascontiguousarray(row_offsets, dtype=np.int64)
+        B = row_offsets.shape[0] - 1
+        K = 0
+        V = target.shape[1]
+        nrows = int(row_offsets[-1]) + B
+        assert target.shape == (nrows, V) and tokens.shape == (nrows - B,)
+        shape = (nrows,)
+    acc = np.empty(B, dtype=np.int32)
+    out = np.empty(shape, dtype=np.int32)
+    amax = np.empty(shape, dtype=np.int32)
+    lib.ears_oracle_verify_greedy(_ptr(target), _ptr(tokens), _ptr(row_offsets), _dtype_code(target),
+                                  B, K, V, _ptr(acc), _ptr(out), _ptr(amax))
+    return acc, out, amax
