@@ -175,6 +175,25 @@ int ears_verify_ex(int dtype, const void* target_logits, const void* draft_logit
                    int32_t* out_accept_len, int32_t* out_tokens, double* out_stats,
                    int32_t* out_path, uint32_t* status_word, void* stream);
 
+/* ---------------------------------------------------------------------------------------------
+ * Temperature -> 0 (greedy decoding, the deterministic regime of the paper's Section 1).  In that
+ * limit p_t and p_d are indicators of their rows' largest logits, R is 1 or 0, the uncertainty
+ * and the tolerance vanish: a draft token is accepted iff it is the arg-max of its target row
+ * (lowest index among equal maxima), and the token after the accepted prefix is the arg-max of
+ * target row n.  No draft logits, no temperature, no random numbers; only target rows are read.
+ *   row_offsets   NULL: rectangular, target [B, K+1, V], draft_tokens [B, K], out_tokens [B, K+1];
+ *                 else packed as for ears_verify_ragged_* (K ignored)
+ *   workspace     device, 256-byte aligned, >= ears_greedy_workspace_bytes() bytes, or NULL to use
+ *                 the library-owned scratch of the simple entry points
+ * Out-of-range draft tokens never match.  Errors as for ears_verify_ex.
+ * ------------------------------------------------------------------------------------------- */
+size_t ears_greedy_workspace_bytes(int64_t total_draft_rows, int B);
+
+int ears_verify_greedy(int dtype, const void* target_logits, const int32_t* draft_tokens,
+                       const int64_t* row_offsets, int64_t total_draft_rows, int B, int K, int V,
+                       void* workspace, size_t workspace_bytes, int32_t* out_accept_len,
+                       int32_t* out_tokens, void* stream);
+
 /* Frees the library-owned scratch of the simple entry points on every device (synchronises). */
 void ears_release(void);
 

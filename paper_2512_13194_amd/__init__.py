@@ -20,10 +20,12 @@ from .binding import (  # noqa: F401
     EarsError,
     ears_bench_copy,
     ears_bench_read,
+    ears_greedy_workspace_bytes,
     ears_release,
     ears_verify_bf16,
     ears_verify_ex,
     ears_verify_f32,
+    ears_verify_greedy,
     ears_verify_ragged_bf16,
     ears_verify_ragged_f32,
     ears_workspace_bytes,

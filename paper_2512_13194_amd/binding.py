@@ -59,6 +59,10 @@ def lib() -> ctypes.CDLL:
         L.ears_verify_ex.argtypes = [i32, vp, vp, vp, vp, i64, i32, i32, i32, f32, f32, vp, vp, i32,
                                      u64, vp, vp, sz, i32, vp, vp, vp, vp, vp, vp]
         L.ears_verify_ex.restype = i32
+        L.ears_greedy_workspace_bytes.argtypes = [i64, i32]
+        L.ears_greedy_workspace_bytes.restype = sz
+        L.ears_verify_greedy.argtypes = [i32, vp, vp, vp, i64, i32, i32, i32, vp, sz, vp, vp, vp]
+        L.ears_verify_greedy.restype = i32
         L.ears_release.argtypes = []
         L.ears_release.restype = None
         L.ears_bench_read_sink_words.argtypes = []
@@ -215,6 +219,45 @@ def ears_verify_ex(target_logits, draft_logits, draft_tokens, *, row_offsets=Non
         _ptr(status_word), _stream(stream)))
     return dict(accept_len=out_accept_len, tokens=out_tokens, stats=stats, path=path,
                 workspace=workspace)
+
+
+def ears_greedy_workspace_bytes(total_draft_rows: int, B: int) -> int:
+    return int(lib().ears_greedy_workspace_bytes(int(total_draft_rows), int(B)))
+
+
+def ears_verify_greedy(target_logits, draft_tokens, *, row_offsets=None, workspace=None,
+                       out_accept_len=None, out_tokens=None, stream=None):
+    """Temperature -> 0 corner.  target [B,K+1,V] + tokens [B,K], or packed target [R+B,V] +
+    tokens [R] + row_offsets [B+1].  Returns (accept_len [B], tokens [B,K+1] or packed [R+B])."""
+    dev = target_logits.device
+    V = target_logits.shape[-1]
+    _need(target_logits, target_logits.dtype, "target_logits")
+    _need(draft_tokens, torch.int32, "draft_tokens")
+    if row_offsets is None:
+        B, K1, _ = target_logits.shape
+        K = K1 - 1
+        R = B * K
+        assert tuple(draft_tokens.shape) == (B, K)
+        shape = (B, K1)
+    else:
+        _need(row_offsets, torch.int64, "row_offsets")
+        B = row_offsets.shape[0] - 1
+        R = draft_tokens.shape[0]
+        K = 0
+        assert tuple(target_logits.shape) == (R + B, V)
+        shape = (R + B,)
+    if out_accept_len is None:
+        out_accept_len = torch.empty(B, dtype=torch.int32, device=dev)
+    if out_tokens is None:
+        out_tokens = torch.empty(shape, dtype=torch.int32, device=dev)
+    _need(out_accept_len, torch.int32, "out_accept_len")
+    _need(out_tokens, torch.int32, "out_tokens")
+    assert out_accept_len.numel() == B and out_tokens.numel() == R + B
+    _check(lib().ears_verify_greedy(
+        _dtype_code(target_logits), _ptr(target_logits), _ptr(draft_tokens), _ptr(row_offsets), R, B,
+        K, V, _ptr(workspace), 0 if workspace is None else workspace.numel(),
+        _ptr(out_accept_len), _ptr(out_tokens), _stream(stream)))
+    return out_accept_len, out_tokens
 
 
 def ears_release() -> None:

@@ -22,6 +22,7 @@
 #include "decide.h"
 #include "ears_device.h"
 #include "row_stats.h"
+#include "greedy.h"
 #include "sample.h"
 
 // Products such as fl(m*c) must stay rounded products (their rounding is undone explicitly
@@ -310,6 +311,57 @@ void ears_release(void) {
     g_scratch_bytes[d] = 0;
   }
   (void)hipSetDevice(prev);
+}
+
+size_t ears_greedy_workspace_bytes(int64_t total_draft_rows, int B) {
+  if (total_draft_rows < 1 || B < 1 || total_draft_rows < B ||
+      total_draft_rows > (int64_t)0x3FFFFFFF)
+    return 0;
+  return align_up((size_t)(total_draft_rows + B) * sizeof(int32_t), 256);
+}
+
+int ears_verify_greedy(int dtype, const void* target_logits, const int32_t* draft_tokens,
+                       const int64_t* row_offsets, int64_t total_draft_rows, int B, int K, int V,
+                       void* workspace, size_t workspace_bytes, int32_t* out_accept_len,
+                       int32_t* out_tokens, void* stream) {
+  if (dtype != EARS_F32 && dtype != EARS_BF16) return EARS_ERR_DTYPE;
+  if (!target_logits || !draft_tokens || !out_accept_len || !out_tokens) return EARS_ERR_NULL;
+  if (B < 1 || V < 1 || total_draft_rows < 1) return EARS_ERR_SHAPE;
+  if (row_offsets == nullptr && (K < 1 || (int64_t)B * (int64_t)K != total_draft_rows))
+    return EARS_ERR_SHAPE;
+  const size_t need = ears_greedy_workspace_bytes(total_draft_rows, B);
+  if (need == 0) return EARS_ERR_SHAPE;
+  if (!aligned(target_logits, 16) || !aligned(draft_tokens, 4) || !aligned(out_accept_len, 4) ||
+      !aligned(out_tokens, 4) || !aligned(row_offsets, 8))
+    return EARS_ERR_ALIGN;
+  if (workspace) {
+    if (workspace_bytes < need) return EARS_ERR_WORKSPACE;
+    if (!aligned(workspace, 256)) return EARS_ERR_ALIGN;
+  } else {
+    const int rc = scratch_get(need, &workspace);
+    if (rc != EARS_OK) return rc;
+  }
+  GreedyProblem p;
+  p.target = target_logits;
+  p.tokens = draft_tokens;
+  p.row_offsets = row_offsets;
+  p.R = total_draft_rows;
+  p.B = B;
+  p.K = K;
+  p.V = V;
+  p.argmax = static_cast<int32_t*>(workspace);
+  p.accept_len = out_accept_len;
+  p.out_tokens = out_tokens;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const int64_t nrows = total_draft_rows + B;
+  const dim3 rows_grid((unsigned)nrows);
+  if (dtype == EARS_F32)
+    hipLaunchKernelGGL((row_argmax_kernel<F32, 4>), rows_grid, dim3(kBlock), 0, s, p);
+  else
+    hipLaunchKernelGGL((row_argmax_kernel<BF16, 4>), rows_grid, dim3(kBlock), 0, s, p);
+  hipLaunchKernelGGL(greedy_scan_kernel, dim3((unsigned)((B + kWavesPerBlock - 1) / kWavesPerBlock)),
+                     dim3(kBlock), 0, s, p);
+  return hipGetLastError() == hipSuccess ? EARS_OK : EARS_ERR_HIP;
 }
 
 int ears_bench_read_sink_words(void) { return kBenchBlocks; }

@@ -35,7 +35,8 @@ class EarsVerifier:
     sampling.  `seed` fixes the whole noise stream: step t of sequence id s always sees the same
     random numbers, whatever slot of the batch the sequence occupies.  `uncertainty` selects what
     scales the tolerance: "maxprob" (the paper's 1 - max P_target) or "entropy" (normalised
-    Shannon entropy, the refinement its Section 5 names).
+    Shannon entropy, the refinement its Section 5 names).  temperature = 0 selects greedy
+    verification (accept while the draft token is the target arg-max): no draft logits, no noise.
     """
 
     UNCERTAINTY = {"maxprob": binding.EARS_UNCERTAINTY_MAXPROB,
@@ -63,8 +64,7 @@ class EarsVerifier:
         """Seed of decode step `step`: the base seed advanced by a Weyl sequence."""
         return (self.seed + (step + 1) * _GOLDEN) & _MASK64
 
-    def _buffers(self, rows: int, B: int, V: int, device) -> None:
-        need = binding.ears_workspace_bytes(rows, B, V)
+    def _buffers(self, rows: int, B: int, need: int, device) -> None:
         if self._workspace is None or self._workspace.numel() < need or self._workspace.device != device:
             self._workspace = torch.empty(need, dtype=torch.uint8, device=device)
         if self._acc is None or self._acc.numel() != B or self._acc.device != device:
@@ -83,6 +83,8 @@ class EarsVerifier:
         """One verification step.  Rectangular: target [B,K+1,V], draft [B,K,V], tokens [B,K].
         Ragged: packed 2-D tensors plus row_offsets [B+1].  The returned tensors are reused by
         the next call."""
+        if self.temperature == 0.0:
+            return self._verify_greedy(target_logits, draft_tokens, row_offsets, step)
         t = self.step if step is None else int(step)
         V = target_logits.shape[-1]
         if row_offsets is None:
@@ -91,7 +93,7 @@ class EarsVerifier:
         else:
             B = row_offsets.shape[0] - 1
             rows = draft_logits.shape[0]
-        self._buffers(rows, B, V, target_logits.device)
+        self._buffers(rows, B, binding.ears_workspace_bytes(rows, B, V), target_logits.device)
         out = binding.ears_verify_ex(
             target_logits, draft_logits, draft_tokens, row_offsets=row_offsets,
             temperature=self.temperature, beta=self.beta, temperature_per_seq=temperature_per_seq,
@@ -106,6 +108,27 @@ class EarsVerifier:
         if self.telemetry:
             self._count(res, rows, B)
         return res
+
+    def _verify_greedy(self, target_logits, draft_tokens, row_offsets, step) -> VerifyResult:
+        if row_offsets is None:
+            B = target_logits.shape[0]
+            rows = B * (target_logits.shape[1] - 1)
+        else:
+            B = row_offsets.shape[0] - 1
+            rows = draft_tokens.shape[0]
+        self._buffers(rows, B, binding.ears_greedy_workspace_bytes(rows, B), target_logits.device)
+        acc, tok = binding.ears_verify_greedy(target_logits, draft_tokens, row_offsets=row_offsets,
+                                              workspace=self._workspace, out_accept_len=self._acc,
+                                              out_tokens=self._tok)
+        if step is None:
+            self.step += 1
+        if self.telemetry:
+            self.counts["positions"] += rows
+            self.counts["sequences"] += B
+            n = int(acc.sum().item())
+            self.counts["accepted_tokens"] += n
+            self.counts["primary"] += n
+        return VerifyResult(acc, tok if row_offsets is not None else tok.view(B, -1))
 
     def _count(self, res: VerifyResult, rows: int, B: int) -> None:
         # one small device-to-host copy per step; telemetry is opt-in

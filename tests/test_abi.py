@@ -137,3 +137,30 @@ def test_binding_and_oracle_do_not_import_each_other():
         if f.endswith((".py", ".c", ".h")):
             src = open(os.path.join(ROOT, "oracle", f)).read()
             assert "paper_2512_13194_amd" not in src and "hip" not in src.lower().replace("relationship", ""), f
+
+
+def _greedy(L, dtype=1, target=P, tokens=P, off=None, R=6, B=2, K=3, V=64, ws=P, wsb=1 << 20,
+            acc=P, out=P):
+    return L.ears_verify_greedy(dtype, target, tokens, off, R, B, K, V, ws, wsb, acc, out, None)
+
+
+def test_greedy_argument_errors(L):
+    from paper_2512_13194_amd import binding as b
+    assert b.ears_greedy_workspace_bytes(2048, 256) == (2048 + 256) * 4
+    assert b.ears_greedy_workspace_bytes(7, 3) % 256 == 0
+    assert b.ears_greedy_workspace_bytes(0, 1) == 0 and b.ears_greedy_workspace_bytes(2, 3) == 0
+    assert _greedy(L, dtype=2) == b.EARS_ERR_DTYPE
+    assert _greedy(L, target=None) == b.EARS_ERR_NULL
+    assert _greedy(L, tokens=None) == b.EARS_ERR_NULL
+    assert _greedy(L, acc=None) == b.EARS_ERR_NULL
+    assert _greedy(L, out=None) == b.EARS_ERR_NULL
+    assert _greedy(L, B=0) == b.EARS_ERR_SHAPE
+    assert _greedy(L, V=0) == b.EARS_ERR_SHAPE
+    assert _greedy(L, K=0) == b.EARS_ERR_SHAPE
+    assert _greedy(L, R=7) == b.EARS_ERR_SHAPE              # rectangular: R must be B*K
+    assert _greedy(L, off=P, R=1, B=2) == b.EARS_ERR_SHAPE  # fewer rows than sequences
+    assert _greedy(L, target=P + 8) == b.EARS_ERR_ALIGN
+    assert _greedy(L, tokens=P + 2) == b.EARS_ERR_ALIGN
+    assert _greedy(L, off=P + 4) == b.EARS_ERR_ALIGN
+    assert _greedy(L, ws=P + 16) == b.EARS_ERR_ALIGN
+    assert _greedy(L, wsb=16) == b.EARS_ERR_WORKSPACE
