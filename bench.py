@@ -154,6 +154,34 @@ def main() -> int:
     read_gbps = k1_bytes * reps / (e0.elapsed_time(e1) * 1e-3) / 1e9
     del rows
 
+    # the two widened paths on the same batch, each as `reps` whole calls between two events
+    def timed_ms(fn, reps=20):
+        for _ in range(3):
+            fn()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(reps):
+            fn()
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) / reps
+
+    ent_ms = timed_ms(lambda: ears.ears_verify_ex(
+        batch.target, batch.draft, batch.tokens, temperature=T, beta=betas[1], seed=seed0,
+        uncertainty=ears.EARS_UNCERTAINTY_ENTROPY, workspace=ws, out_accept_len=acc,
+        out_tokens=tok.view(-1)))
+    greedy_tokens = batch.target[:, :K].float().argmax(-1).to(torch.int32)
+    greedy_tokens[::2, K // 2] = 0        # half of the sequences stop in the middle
+    greedy_ms = timed_ms(lambda: ears.ears_verify_greedy(
+        batch.target, greedy_tokens, workspace=ws, out_accept_len=acc, out_tokens=tok))
+    greedy_bytes = B * (K + 1) * V * esz
+    other_paths = {
+        "entropy_uncertainty": {"ms_per_call": ent_ms, "positions_per_s": B * K / (ent_ms * 1e-3)},
+        "greedy_temperature_0": {"ms_per_call": greedy_ms,
+                                 "positions_per_s": B * K / (greedy_ms * 1e-3),
+                                 "algorithmic_bytes": greedy_bytes,
+                                 "achieved_GBps": greedy_bytes / (greedy_ms * 1e-3) / 1e9}}
+
     if args.traffic_calibration:
         # plain copy of the draft buffer: reads and writes exactly draft.numel() * 2 bytes
         dst = torch.empty_like(batch.draft)
@@ -208,6 +236,7 @@ def main() -> int:
                      "avg_launch_ms": k1_ms,
                      "stream_read_ceiling_GBps": read_gbps},
         "cpu_baseline": cpu,
+        "other_paths": other_paths,
     }
     print(json.dumps(out), flush=True)
     return 0
