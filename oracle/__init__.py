@@ -14,6 +14,9 @@ from .ears_oracle import (  # noqa: F401
     build,
     gumbel,
     gumbel_uniform,
+    lm_head,
+    lm_head_dot,
+    round_bf16,
     philox4x32_10,
     softmax,
     verify,

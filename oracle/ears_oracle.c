@@ -325,3 +325,55 @@ void ears_oracle_verify_greedy(const void* target, const int32_t* tokens,
     }
   }
 }
+
+/* ------------------------------------------------------------------------------------------ */
+/* Producer side (Section 3.3 item 1: the statistics are taken "immediately after the target
+ * model's forward pass"): the last step of that pass is the vocabulary projection
+ * logits[n, v] = sum_k hidden[n, k] * weight[v, k], stored as bfloat16.  Plain fp64 dot products
+ * of the bf16 inputs; round-to-nearest-even to bf16 is a separate, explicit step. */
+static double bf16_value(uint16_t bits) {
+  uint32_t w = (uint32_t)bits << 16;
+  float f;
+  memcpy(&f, &w, sizeof f);
+  return (double)f;
+}
+
+double ears_oracle_lm_head_dot(const uint16_t* hidden, const uint16_t* weight, int D, int64_t n,
+                               int64_t v) {
+  double acc = 0.0;
+  for (int k = 0; k < D; ++k)
+    acc += bf16_value(hidden[(size_t)n * D + k]) * bf16_value(weight[(size_t)v * D + k]);
+  return acc;
+}
+
+/* Nearest bfloat16 (ties to even) of a finite double that is not near the overflow threshold:
+ * keep 8 significant bits.  Written with frexp/nearbyint, not with bit tricks, so that it can be
+ * read against the definition of the format (1 sign, 8 exponent, 7 fraction bits). */
+uint16_t ears_oracle_round_bf16(double x) {
+  if (x == 0.0) return signbit(x) ? 0x8000u : 0u;
+  int e;
+  double m = frexp(fabs(x), &e);          /* |x| = m * 2^e, m in [0.5, 1) */
+  if (e - 1 < -126) {                      /* below the normal range: fixed spacing 2^-133 */
+    double q = nearbyint(ldexp(fabs(x), 133));
+    return (uint16_t)((signbit(x) ? 0x8000u : 0u) | (uint16_t)q);
+  }
+  double q = nearbyint(ldexp(m, 8));      /* 8 significant bits: q in [128, 256] */
+  if (q == 256.0) {
+    q = 128.0;
+    e += 1;
+  }
+  unsigned biased = (unsigned)(e - 1 + 127);
+  return (uint16_t)((signbit(x) ? 0x8000u : 0u) | (biased << 7) | ((unsigned)q - 128u));
+}
+
+void ears_oracle_lm_head(const uint16_t* hidden, const uint16_t* weight, int N, int D, int V,
+                         double* exact, uint16_t* logits, int nthreads) {
+  if (nthreads < 1) nthreads = 1;
+#pragma omp parallel for num_threads(nthreads) schedule(static)
+  for (int n = 0; n < N; ++n)
+    for (int v = 0; v < V; ++v) {
+      double x = ears_oracle_lm_head_dot(hidden, weight, D, n, v);
+      if (exact) exact[(size_t)n * V + v] = x;
+      if (logits) logits[(size_t)n * V + v] = ears_oracle_round_bf16(x);
+    }
+}

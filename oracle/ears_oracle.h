@@ -127,6 +127,15 @@ void ears_oracle_verify_greedy(const void* target, const int32_t* tokens,
                                const int64_t* row_offsets, int dtype, int B, int K, int V,
                                int32_t* accept_len, int32_t* out_tokens, int32_t* target_argmax);
 
+/* Vocabulary projection that produces the logits: hidden [N, D] and weight [V, D] are bf16 bit
+ * patterns; exact[n, v] = sum_k hidden[n,k] * weight[v,k] in fp64 (optional), logits[n, v] its
+ * nearest bf16 (optional). */
+double ears_oracle_lm_head_dot(const uint16_t* hidden, const uint16_t* weight, int D, int64_t n,
+                               int64_t v);
+uint16_t ears_oracle_round_bf16(double x);
+void ears_oracle_lm_head(const uint16_t* hidden, const uint16_t* weight, int N, int D, int V,
+                         double* exact, uint16_t* logits, int nthreads);
+
 #ifdef __cplusplus
 }
 #endif

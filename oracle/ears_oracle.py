@@ -76,6 +76,13 @@ def _load():
     lib.ears_oracle_verify_greedy.argtypes = [c.c_void_p, c.c_void_p, c.c_void_p, c.c_int, c.c_int,
                                               c.c_int, c.c_int, c.c_void_p, c.c_void_p, c.c_void_p]
     lib.ears_oracle_verify_greedy.restype = None
+    lib.ears_oracle_lm_head_dot.argtypes = [c.c_void_p, c.c_void_p, c.c_int, c.c_int64, c.c_int64]
+    lib.ears_oracle_lm_head_dot.restype = c.c_double
+    lib.ears_oracle_round_bf16.argtypes = [c.c_double]
+    lib.ears_oracle_round_bf16.restype = c.c_uint16
+    lib.ears_oracle_lm_head.argtypes = [c.c_void_p, c.c_void_p, c.c_int, c.c_int, c.c_int,
+                                        c.c_void_p, c.c_void_p, c.c_int]
+    lib.ears_oracle_lm_head.restype = None
     _lib = lib
     return lib
 
@@ -236,3 +243,32 @@ def verify_greedy(target: np.ndarray, tokens: np.ndarray, row_offsets: Optional[
     lib.ears_oracle_verify_greedy(_ptr(target), _ptr(tokens), _ptr(row_offsets), _dtype_code(target),
                                   B, K, V, _ptr(acc), _ptr(out), _ptr(amax))
     return acc, out, amax
+
+
+def round_bf16(x: float) -> int:
+    """Bit pattern of the bfloat16 nearest to x (ties to even)."""
+    return int(_load().ears_oracle_round_bf16(float(x)))
+
+
+def lm_head_dot(hidden: np.ndarray, weight: np.ndarray, n: int, v: int) -> float:
+    """One logit, sum_k hidden[n,k] * weight[v,k], in fp64; inputs are uint16 bf16 bit patterns."""
+    assert hidden.dtype == np.uint16 and weight.dtype == np.uint16
+    assert hidden.flags.c_contiguous and weight.flags.c_contiguous
+    assert hidden.shape[1] == weight.shape[1]
+    return float(_load().ears_oracle_lm_head_dot(_ptr(hidden), _ptr(weight), hidden.shape[1],
+                                                 int(n), int(v)))
+
+
+def lm_head(hidden: np.ndarray, weight: np.ndarray, nthreads: int = 1):
+    """Vocabulary projection: returns (exact [N,V] float64, logits [N,V] uint16 bf16 bits)."""
+    hidden = np.ascontiguousarray(hidden)
+    weight = np.ascontiguousarray(weight)
+    assert hidden.dtype == np.uint16 and weight.dtype == np.uint16
+    N, D = hidden.shape
+    V = weight.shape[0]
+    assert weight.shape[1] == D
+    exact = np.empty((N, V), dtype=np.float64)
+    logits = np.empty((N, V), dtype=np.uint16)
+    _load().ears_oracle_lm_head(_ptr(hidden), _ptr(weight), N, D, V, _ptr(exact), _ptr(logits),
+                                int(nthreads))
+    return exact, logits
