@@ -194,6 +194,44 @@ int ears_verify_greedy(int dtype, const void* target_logits, const int32_t* draf
                        void* workspace, size_t workspace_bytes, int32_t* out_accept_len,
                        int32_t* out_tokens, void* stream);
 
+/* ---------------------------------------------------------------------------------------------
+ * Producer-side fusion (Section 3.3 item 1: max P_t is computed "immediately after the target
+ * model's forward pass" and cached).  The last step of that pass, the vocabulary projection
+ *   logits[n, v] = sum_k hidden[n, k] * weight[v, k]      (bf16 inputs, fp32 accumulation, MFMA)
+ * is computed here with an epilogue that rounds each logit to bf16 (nearest even), writes it once,
+ * and takes the statistics of the ROUNDED row at temperature T while it is still in registers:
+ *   out_row_max[n]    = max_v logits[n, v]
+ *   out_row_sumexp[n] = sum_v exp((logits[n, v] - max) / T)        (so max_v p(v) = 1 / sumexp)
+ * exactly the per-row quantities the statistics stage of ears_verify_ex would otherwise obtain by
+ * re-reading the logits.  ears_import_stats() hands them to a verification workspace.
+ *   hidden  [N, D] bf16, weight [V, D] bf16 (both row-major, 16-byte aligned); D a multiple of 64
+ *   temperature      scalar T > 0, used when row_temperature is NULL
+ *   row_temperature  device [N] float or NULL
+ *   out_logits       [N, V] bf16;  out_row_max [N] float;  out_row_sumexp [N] double
+ *   workspace        device, 256-byte aligned, >= ears_lm_head_workspace_bytes(N, V) bytes
+ * N * V must be below 2^31.
+ * ------------------------------------------------------------------------------------------- */
+size_t ears_lm_head_workspace_bytes(int N, int V);
+
+int ears_lm_head_bf16(const void* hidden, const void* weight, int N, int D, int V,
+                      float temperature, const float* row_temperature, void* out_logits,
+                      float* out_row_max, double* out_row_sumexp, void* workspace,
+                      size_t workspace_bytes, void* stream);
+
+/* Fills the statistics part of a verification workspace from per-row statistics computed by the
+ * producers of the logits (ears_lm_head_bf16 for the target and for the draft model), and gathers
+ * the draft tokens' logits.  Afterwards ears_verify_ex with stages DECIDE | SAMPLE (same batch,
+ * same temperature(s), EARS_UNCERTAINTY_MAXPROB) completes the step without the statistics pass.
+ *   target_row_max / target_row_sumexp   [total_draft_rows + B], packed like the target rows
+ *   draft_row_max / draft_row_sumexp     [total_draft_rows]
+ * Other arguments as for ears_verify_ex. */
+int ears_import_stats(int dtype, const void* target_logits, const void* draft_logits,
+                      const int32_t* draft_tokens, const int64_t* row_offsets,
+                      int64_t total_draft_rows, int B, int K, int V, const float* target_row_max,
+                      const double* target_row_sumexp, const float* draft_row_max,
+                      const double* draft_row_sumexp, void* workspace, size_t workspace_bytes,
+                      void* stream);
+
 /* Frees the library-owned scratch of the simple entry points on every device (synchronises). */
 void ears_release(void);
 

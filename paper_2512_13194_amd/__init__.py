@@ -21,6 +21,9 @@ from .binding import (  # noqa: F401
     ears_bench_copy,
     ears_bench_read,
     ears_greedy_workspace_bytes,
+    ears_import_stats,
+    ears_lm_head_bf16,
+    ears_lm_head_workspace_bytes,
     ears_release,
     ears_verify_bf16,
     ears_verify_ex,

@@ -63,6 +63,13 @@ def lib() -> ctypes.CDLL:
         L.ears_greedy_workspace_bytes.restype = sz
         L.ears_verify_greedy.argtypes = [i32, vp, vp, vp, i64, i32, i32, i32, vp, sz, vp, vp, vp]
         L.ears_verify_greedy.restype = i32
+        L.ears_lm_head_workspace_bytes.argtypes = [i32, i32]
+        L.ears_lm_head_workspace_bytes.restype = sz
+        L.ears_lm_head_bf16.argtypes = [vp, vp, i32, i32, i32, f32, vp, vp, vp, vp, vp, sz, vp]
+        L.ears_lm_head_bf16.restype = i32
+        L.ears_import_stats.argtypes = [i32, vp, vp, vp, vp, i64, i32, i32, i32, vp, vp, vp, vp, vp,
+                                        sz, vp]
+        L.ears_import_stats.restype = i32
         L.ears_release.argtypes = []
         L.ears_release.restype = None
         L.ears_bench_read_sink_words.argtypes = []
@@ -258,6 +265,67 @@ def ears_verify_greedy(target_logits, draft_tokens, *, row_offsets=None, workspa
         K, V, _ptr(workspace), 0 if workspace is None else workspace.numel(),
         _ptr(out_accept_len), _ptr(out_tokens), _stream(stream)))
     return out_accept_len, out_tokens
+
+
+def ears_lm_head_workspace_bytes(N: int, V: int) -> int:
+    return int(lib().ears_lm_head_workspace_bytes(int(N), int(V)))
+
+
+def ears_lm_head_bf16(hidden, weight, *, temperature=1.0, row_temperature=None, out_logits=None,
+                      out_row_max=None, out_row_sumexp=None, workspace=None, stream=None):
+    """hidden [N,D] bf16, weight [V,D] bf16 -> (logits [N,V] bf16, row_max [N] f32, row_sumexp [N] f64)."""
+    _need(hidden, torch.bfloat16, "hidden")
+    _need(weight, torch.bfloat16, "weight")
+    N, D = hidden.shape
+    V = weight.shape[0]
+    assert weight.shape[1] == D
+    dev = hidden.device
+    if out_logits is None:
+        out_logits = torch.empty(N, V, dtype=torch.bfloat16, device=dev)
+    if out_row_max is None:
+        out_row_max = torch.empty(N, dtype=torch.float32, device=dev)
+    if out_row_sumexp is None:
+        out_row_sumexp = torch.empty(N, dtype=torch.float64, device=dev)
+    if workspace is None:
+        workspace = torch.empty(max(ears_lm_head_workspace_bytes(N, V), 1), dtype=torch.uint8, device=dev)
+    _need(out_logits, torch.bfloat16, "out_logits")
+    _need(out_row_max, torch.float32, "out_row_max")
+    _need(out_row_sumexp, torch.float64, "out_row_sumexp")
+    assert tuple(out_logits.shape) == (N, V) and out_row_max.numel() == N and out_row_sumexp.numel() == N
+    if row_temperature is not None:
+        _need(row_temperature, torch.float32, "row_temperature")
+        assert row_temperature.numel() == N
+    _check(lib().ears_lm_head_bf16(_ptr(hidden), _ptr(weight), N, D, V, float(temperature),
+                                   _ptr(row_temperature), _ptr(out_logits), _ptr(out_row_max),
+                                   _ptr(out_row_sumexp), _ptr(workspace), workspace.numel(),
+                                   _stream(stream)))
+    return out_logits, out_row_max, out_row_sumexp
+
+
+def ears_import_stats(target_logits, draft_logits, draft_tokens, target_row_max, target_row_sumexp,
+                      draft_row_max, draft_row_sumexp, workspace, *, row_offsets=None, stream=None):
+    """Fills `workspace` (uint8 CUDA tensor of ears_workspace_bytes) with producer-side statistics."""
+    V = target_logits.shape[-1]
+    if row_offsets is None:
+        B, K1, _ = target_logits.shape
+        K = K1 - 1
+        R = B * K
+    else:
+        B = row_offsets.shape[0] - 1
+        R = draft_logits.shape[0]
+        K = 0
+    _need(target_row_max, torch.float32, "target_row_max")
+    _need(draft_row_max, torch.float32, "draft_row_max")
+    _need(target_row_sumexp, torch.float64, "target_row_sumexp")
+    _need(draft_row_sumexp, torch.float64, "draft_row_sumexp")
+    assert target_row_max.numel() == R + B == target_row_sumexp.numel()
+    assert draft_row_max.numel() == R == draft_row_sumexp.numel()
+    _check(lib().ears_import_stats(
+        _dtype_code(target_logits), _ptr(target_logits), _ptr(draft_logits), _ptr(draft_tokens),
+        _ptr(row_offsets), R, B, K, V, _ptr(target_row_max), _ptr(target_row_sumexp),
+        _ptr(draft_row_max), _ptr(draft_row_sumexp), _ptr(workspace), workspace.numel(),
+        _stream(stream)))
+    return workspace
 
 
 def ears_release() -> None:

@@ -23,6 +23,7 @@
 #include "ears_device.h"
 #include "row_stats.h"
 #include "greedy.h"
+#include "lm_head.h"
 #include "sample.h"
 
 // Products such as fl(m*c) must stay rounded products (their rounding is undone explicitly
@@ -361,6 +362,94 @@ int ears_verify_greedy(int dtype, const void* target_logits, const int32_t* draf
     hipLaunchKernelGGL((row_argmax_kernel<BF16, 4>), rows_grid, dim3(kBlock), 0, s, p);
   hipLaunchKernelGGL(greedy_scan_kernel, dim3((unsigned)((B + kWavesPerBlock - 1) / kWavesPerBlock)),
                      dim3(kBlock), 0, s, p);
+  return hipGetLastError() == hipSuccess ? EARS_OK : EARS_ERR_HIP;
+}
+
+size_t ears_lm_head_workspace_bytes(int N, int V) {
+  if (N < 1 || V < 1) return 0;
+  const size_t nparts = (size_t)kLmPartsPerTile * (size_t)((V + kLmTile - 1) / kLmTile);
+  return 2 * align_up((size_t)N * nparts * sizeof(float), 256);
+}
+
+int ears_lm_head_bf16(const void* hidden, const void* weight, int N, int D, int V,
+                      float temperature, const float* row_temperature, void* out_logits,
+                      float* out_row_max, double* out_row_sumexp, void* workspace,
+                      size_t workspace_bytes, void* stream) {
+  if (!hidden || !weight || !out_logits || !out_row_max || !out_row_sumexp) return EARS_ERR_NULL;
+  if (N < 1 || V < 1 || D < kLmBK || D % kLmBK != 0) return EARS_ERR_SHAPE;
+  if ((int64_t)N * (int64_t)V > (int64_t)0x7FFFFFFF) return EARS_ERR_SHAPE;
+  if (!row_temperature && !(std::isfinite(temperature) && temperature > 0.0f)) return EARS_ERR_PARAM;
+  if (!aligned(hidden, 16) || !aligned(weight, 16) || !aligned(out_logits, 2) ||
+      !aligned(out_row_max, 4) || !aligned(out_row_sumexp, 8) || !aligned(row_temperature, 4))
+    return EARS_ERR_ALIGN;
+  const size_t need = ears_lm_head_workspace_bytes(N, V);
+  if (!workspace || workspace_bytes < need) return EARS_ERR_WORKSPACE;
+  if (!aligned(workspace, 256)) return EARS_ERR_ALIGN;
+  LmHeadProblem p;
+  p.hidden = static_cast<const uint16_t*>(hidden);
+  p.weight = static_cast<const uint16_t*>(weight);
+  p.row_T = row_temperature;
+  p.T = temperature;
+  p.N = N;
+  p.D = D;
+  p.V = V;
+  p.n_vtiles = (V + kLmTile - 1) / kLmTile;
+  p.n_ttiles = (N + kLmTile - 1) / kLmTile;
+  p.logits = static_cast<uint16_t*>(out_logits);
+  p.nparts = kLmPartsPerTile * p.n_vtiles;
+  p.part_m = static_cast<float*>(workspace);
+  p.part_S = reinterpret_cast<float*>(static_cast<unsigned char*>(workspace) + need / 2);
+  p.row_m = out_row_max;
+  p.row_Z = out_row_sumexp;
+  const int64_t groups = (int64_t)8 * ((p.n_vtiles + 7) / 8) * p.n_ttiles;
+  if (groups > (int64_t)0x7FFFFFFF) return EARS_ERR_SHAPE;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  hipLaunchKernelGGL(lm_head_kernel, dim3((unsigned)groups), dim3(kLmThreads), 0, s, p);
+  hipLaunchKernelGGL(lm_head_merge_kernel, dim3((unsigned)((N + kWavesPerBlock - 1) / kWavesPerBlock)),
+                     dim3(kBlock), 0, s, p);
+  return hipGetLastError() == hipSuccess ? EARS_OK : EARS_ERR_HIP;
+}
+
+int ears_import_stats(int dtype, const void* target_logits, const void* draft_logits,
+                      const int32_t* draft_tokens, const int64_t* row_offsets,
+                      int64_t total_draft_rows, int B, int K, int V, const float* target_row_max,
+                      const double* target_row_sumexp, const float* draft_row_max,
+                      const double* draft_row_sumexp, void* workspace, size_t workspace_bytes,
+                      void* stream) {
+  if (!target_row_max || !target_row_sumexp || !draft_row_max || !draft_row_sumexp)
+    return EARS_ERR_NULL;
+  WorkspaceLayout lay;
+  // the output pointers of a verification call are not involved: stand-ins pass its null checks
+  const int32_t* stand_in = draft_tokens;
+  const int rc = validate(dtype, target_logits, draft_logits, draft_tokens, row_offsets,
+                          total_draft_rows, B, K, V, 1.0f, 0.0f, nullptr, nullptr, nullptr, workspace,
+                          workspace_bytes, EARS_STAGE_STATS, stand_in, stand_in, nullptr, nullptr,
+                          nullptr, &lay);
+  if (rc != EARS_OK) return rc;
+  if (!aligned(target_row_max, 4) || !aligned(draft_row_max, 4) || !aligned(target_row_sumexp, 8) ||
+      !aligned(draft_row_sumexp, 8))
+    return EARS_ERR_ALIGN;
+  Problem p = {};
+  p.target = target_logits;
+  p.draft = draft_logits;
+  p.tokens = draft_tokens;
+  p.row_offsets = row_offsets;
+  p.R = total_draft_rows;
+  p.B = B;
+  p.K = K;
+  p.V = V;
+  unsigned char* ws = static_cast<unsigned char*>(workspace);
+  p.Z = reinterpret_cast<double*>(ws + lay.off_Z);
+  p.m = reinterpret_cast<float*>(ws + lay.off_m);
+  p.lx = reinterpret_cast<float*>(ws + lay.off_lx);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const dim3 grid((unsigned)((total_draft_rows + kBlock - 1) / kBlock));
+  if (dtype == EARS_F32)
+    hipLaunchKernelGGL(import_stats_kernel<F32>, grid, dim3(kBlock), 0, s, p, target_row_max,
+                       target_row_sumexp, draft_row_max, draft_row_sumexp);
+  else
+    hipLaunchKernelGGL(import_stats_kernel<BF16>, grid, dim3(kBlock), 0, s, p, target_row_max,
+                       target_row_sumexp, draft_row_max, draft_row_sumexp);
   return hipGetLastError() == hipSuccess ? EARS_OK : EARS_ERR_HIP;
 }
 

@@ -1,0 +1,274 @@
+// Producer-side fusion (paper Section 3.3 item 1: the statistics are computed "immediately after the
+// target model's forward pass"): the vocabulary projection logits[n, v] = sum_k hidden[n, k] *
+// weight[v, k] on the matrix cores, whose epilogue rounds the logits to bf16, takes the softmax
+// statistics (row maximum, sum of exponentials) of the rounded values while they are still in
+// registers, and writes the logits once.  The verification step then starts from cached statistics
+// and never re-reads the logits for them.
+//
+// One workgroup (4 waves) computes a 256 (vocabulary) x 256 (tokens) tile; each wave owns 128 x 128
+// as 4 x 4 blocks of v_mfma_f32_32x32x16_bf16 with the vocabulary on the MFMA's row index, so that a
+// lane's 16 accumulator registers of a block are 16 vocabulary entries of ONE token and the
+// statistics start as in-lane reductions.
+#pragma once
+
+#include "ears_device.h"
+
+namespace ears {
+
+constexpr int kLmTile = 256;          // tile edge, vocabulary and tokens
+constexpr int kLmBK = 64;             // depth of one staged slab (bf16 elements): 128 bytes per row
+constexpr int kLmThreads = 256;       // 4 waves as 2 (vocabulary) x 2 (tokens)
+constexpr int kLmWaveTile = 128;
+constexpr int kLmSlabBytes = kLmTile * kLmBK * 2;            // 32 KiB per operand per buffer
+constexpr int kLmStageRow = kLmTile * 2 + 8;                 // epilogue staging: 520-byte token rows
+constexpr int kLmSharedBytes = kLmTile * kLmStageRow;        // 133 120 B >= 4 slabs (131 072 B)
+constexpr int kLmPartsPerTile = 2;                           // one partial per wave row of a tile
+
+struct LmHeadProblem {
+  const uint16_t* hidden;   // [N, D] bf16
+  const uint16_t* weight;   // [V, D] bf16
+  const float* row_T;       // [N] per-row temperature or nullptr
+  float T;
+  int N, D, V;
+  int n_vtiles, n_ttiles;   // tiles along the vocabulary and along the tokens
+  uint16_t* logits;         // [N, V] bf16
+  float* part_m;            // [N, nparts] maximum of the rounded logits of one 128-entry slice
+  float* part_S;            // [N, nparts] sum of exp2(l*c - fl(m*c)) over the slice
+  int nparts;               // 2 * n_vtiles
+  float* row_m;             // [N]
+  double* row_Z;            // [N]
+};
+
+typedef __bf16 lm_bf16x8 __attribute__((ext_vector_type(8)));
+typedef float lm_f32x16 __attribute__((ext_vector_type(16)));
+
+// 16-byte chunk c (0..7) of slab row `row` lives at chunk position c ^ swizzle(row): 8 or 16
+// consecutive rows then spread over all banks for both the 16-byte fragment reads and the writes.
+__device__ __forceinline__ int lm_swizzle(int row) { return (row & 7) ^ ((row >> 3) & 1); }
+
+__device__ __forceinline__ uint16_t lm_round_bf16(float x) {
+  return __builtin_bit_cast(uint16_t, (__bf16)x);  // round to nearest even
+}
+
+__global__ __launch_bounds__(kLmThreads) __attribute__((amdgpu_waves_per_eu(1, 1)))
+void lm_head_kernel(LmHeadProblem p) {
+  __shared__ __attribute__((aligned(16))) unsigned char smem[kLmSharedBytes];
+
+  // Workgroup ids go round-robin over the 8 XCDs.  The token tiles that share a vocabulary tile
+  // (hence the same weight rows) get consecutive ids on ONE XCD, so the weights reach each L2 once.
+  const int id = (int)blockIdx.x;
+  const int xcd = id & 7, local = id >> 3;
+  const int vt = (local / p.n_ttiles) * 8 + xcd;
+  const int tt = local % p.n_ttiles;
+  if (vt >= p.n_vtiles) return;  // uniform over the workgroup
+  const int v0 = vt * kLmTile, n0 = tt * kLmTile;
+
+  const int tid = (int)threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6;
+  const int wv = wave >> 1, wn = wave & 1;  // wave's 128-slice along vocabulary / tokens
+
+  // ---- global -> LDS staging: thread owns chunk (tid & 7) of rows (tid >> 3) + 32 j, j = 0..7 ----
+  const int st_chunk = tid & 7, st_row = tid >> 3;
+  const int st_off = st_row * (kLmBK * 2) + ((st_chunk ^ lm_swizzle(st_row)) << 4);
+  const uint4* gA[8];
+  const uint4* gB[8];
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    int rv = v0 + st_row + 32 * j;
+    int rn = n0 + st_row + 32 * j;
+    rv = rv < p.V ? rv : p.V - 1;  // rows past the edge re-read the last row; their results are dropped
+    rn = rn < p.N ? rn : p.N - 1;
+    gA[j] = reinterpret_cast<const uint4*>(p.weight + (size_t)rv * p.D + st_chunk * 8);
+    gB[j] = reinterpret_cast<const uint4*>(p.hidden + (size_t)rn * p.D + st_chunk * 8);
+  }
+
+  // ---- fragment reads: lane supplies row (lane & 31), k-offset 8 * (lane >> 5) of each block ----
+  const int fr_swz = lm_swizzle(lane & 31);
+  int fr_off[4];
+#pragma unroll
+  for (int s = 0; s < 4; ++s) fr_off[s] = (lane & 31) * (kLmBK * 2) + (((2 * s + (lane >> 5)) ^ fr_swz) << 4);
+  const int fr_A = wv * kLmWaveTile * (kLmBK * 2);
+  const int fr_B = wn * kLmWaveTile * (kLmBK * 2);
+
+  lm_f32x16 acc[4][4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+
+  const int n_slabs = p.D / kLmBK;
+  uint4 ra[8], rb[8];
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    ra[j] = *gA[j];
+    rb[j] = *gB[j];
+  }
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    *reinterpret_cast<uint4*>(smem + st_off + j * 32 * (kLmBK * 2)) = ra[j];
+    *reinterpret_cast<uint4*>(smem + kLmSlabBytes + st_off + j * 32 * (kLmBK * 2)) = rb[j];
+  }
+  __syncthreads();
+
+  for (int slab = 0; slab < n_slabs; ++slab) {
+    const int cur = (slab & 1) * 2 * kLmSlabBytes;
+    const int nxt = ((slab + 1) & 1) * 2 * kLmSlabBytes;
+    const bool more = slab + 1 < n_slabs;  // uniform
+    if (more) {
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        ra[j] = *(gA[j] + (size_t)(slab + 1) * (kLmBK / 8));
+        rb[j] = *(gB[j] + (size_t)(slab + 1) * (kLmBK / 8));
+      }
+    }
+    const unsigned char* sA = smem + cur + fr_A;
+    const unsigned char* sB = smem + cur + kLmSlabBytes + fr_B;
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+      lm_bf16x8 fa[4], fb[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        fa[i] = *reinterpret_cast<const lm_bf16x8*>(sA + fr_off[s] + i * 32 * (kLmBK * 2));
+        fb[i] = *reinterpret_cast<const lm_bf16x8*>(sB + fr_off[s] + i * 32 * (kLmBK * 2));
+      }
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+    }
+    if (more) {
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        *reinterpret_cast<uint4*>(smem + nxt + st_off + j * 32 * (kLmBK * 2)) = ra[j];
+        *reinterpret_cast<uint4*>(smem + nxt + kLmSlabBytes + st_off + j * 32 * (kLmBK * 2)) = rb[j];
+      }
+    }
+    __syncthreads();
+  }
+
+  // ---- epilogue ------------------------------------------------------------------------------
+  // acc[i][j][r] is vocabulary entry v0 + wv*128 + i*32 + 8*(r/4) + 4*(lane/32) + r%4 of token
+  // n0 + wn*128 + j*32 + lane%32.  Round, take the statistics of the rounded values, stage the
+  // tile as [token][vocabulary] rows and write them out whole.
+  const int half = lane >> 5;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const int tok_local = wn * kLmWaveTile + j * 32 + (lane & 31);
+    const int tok = n0 + tok_local;
+    const float T = p.row_T ? p.row_T[tok < p.N ? tok : p.N - 1] : p.T;
+    const float c = (float)(kLog2e / (double)T);
+    float xr[4][16];
+    float m = -INFINITY;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const int v_local = wv * kLmWaveTile + i * 32 + 8 * g + 4 * half;
+        uint16_t b[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          b[q] = lm_round_bf16(acc[i][j][4 * g + q]);
+          const float x = __uint_as_float((uint32_t)b[q] << 16);
+          const bool valid = v0 + v_local + q < p.V;
+          xr[i][4 * g + q] = valid ? x : -INFINITY;
+          m = fmaxf(m, xr[i][4 * g + q]);
+        }
+        uint2 packed;
+        packed.x = (uint32_t)b[0] | ((uint32_t)b[1] << 16);
+        packed.y = (uint32_t)b[2] | ((uint32_t)b[3] << 16);
+        *reinterpret_cast<uint2*>(smem + tok_local * kLmStageRow + v_local * 2) = packed;
+      }
+    }
+    // the other half-wave holds the other 64 entries of the same token's 128-slice
+    m = fmaxf(m, __shfl_xor(m, 32, 64));
+    float S = 0.0f;
+    if (m != -INFINITY) {
+      const float mc = m * c;
+      float s4[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) s4[r & 3] += __builtin_amdgcn_exp2f(fmaf(xr[i][r], c, -mc));
+      S = (s4[0] + s4[1]) + (s4[2] + s4[3]);
+    }
+    S += __shfl_xor(S, 32, 64);
+    if (half == 0 && tok < p.N) {
+      const size_t slot = (size_t)tok * p.nparts + vt * kLmPartsPerTile + wv;
+      p.part_m[slot] = m;
+      p.part_S[slot] = S;
+    }
+  }
+  __syncthreads();
+  // whole rows out: a wave writes one 512-byte token row per instruction (8 bytes per lane)
+  const int v_lane = v0 + lane * 4;
+  for (int row = wave; row < kLmTile; row += kLmThreads / 64) {
+    const int tok = n0 + row;
+    if (tok >= p.N) break;  // uniform over the wave
+    const uint2 val = *reinterpret_cast<const uint2*>(smem + row * kLmStageRow + lane * 8);
+    uint16_t* dst = p.logits + (size_t)tok * p.V + v_lane;
+    if (v_lane + 3 < p.V && ((reinterpret_cast<uintptr_t>(dst) & 7u) == 0)) {
+      *reinterpret_cast<uint2*>(dst) = val;
+    } else {
+      const uint16_t e[4] = {(uint16_t)(val.x & 0xFFFFu), (uint16_t)(val.x >> 16),
+                             (uint16_t)(val.y & 0xFFFFu), (uint16_t)(val.y >> 16)};
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
+        if (v_lane + q < p.V) dst[q] = e[q];
+    }
+  }
+}
+
+// Merges the per-slice partials of one token row with the associative rule of the statistics pass:
+// M = max m, Z = sum S * 2^(fl(m c) - fl(M c)) in fp64, then the rounding of fl(M c) undone.
+__global__ __launch_bounds__(kBlock) void lm_head_merge_kernel(LmHeadProblem p) {
+  const int lane = (int)threadIdx.x & (kWave - 1);
+  const int row = (int)blockIdx.x * kWavesPerBlock + (int)threadIdx.x / kWave;
+  if (row >= p.N) return;  // uniform over the wave
+  const float T = p.row_T ? p.row_T[row] : p.T;
+  const float c = (float)(kLog2e / (double)T);
+  const float* pm = p.part_m + (size_t)row * p.nparts;
+  const float* pS = p.part_S + (size_t)row * p.nparts;
+  float M = -INFINITY;
+  for (int i = lane; i < p.nparts; i += kWave) M = fmaxf(M, pm[i]);
+  M = wave_max(M);
+  const float Mc = M * c;
+  double Z = 0.0;
+  for (int i = lane; i < p.nparts; i += kWave) {
+    const float m = pm[i];
+    if (m != -INFINITY) Z += (double)pS[i] * exp2((double)(m * c) - (double)Mc);
+  }
+  Z = wave_sum(Z);
+  if (lane == 0) {
+    p.row_m[row] = M;
+    p.row_Z[row] = Z * exp2((double)Mc - (double)M * (double)c);
+  }
+}
+
+// Hands producer-side statistics to the verification workspace: draft position r of sequence b
+// pairs target row r + b with draft row r (the layout the statistics pass writes).
+template <typename DT>
+__global__ __launch_bounds__(kBlock) void import_stats_kernel(Problem p, const float* t_max,
+                                                               const double* t_sum,
+                                                               const float* d_max,
+                                                               const double* d_sum) {
+  const int64_t r = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  if (r >= p.R) return;
+  const int b = seq_of_row(p, r);
+  const int32_t x = p.tokens[r];
+  float lxt = -INFINITY, lxd = -INFINITY;
+  if (x >= 0 && x < p.V) {
+    lxt = DT::load(p.target, (r + b) * (int64_t)p.V + x);
+    lxd = DT::load(p.draft, r * (int64_t)p.V + x);
+  }
+  p.Z[2 * r] = t_sum[r + b];
+  p.Z[2 * r + 1] = d_sum[r];
+  p.m[2 * r] = t_max[r + b];
+  p.m[2 * r + 1] = d_max[r];
+  p.lx[2 * r] = lxt;
+  p.lx[2 * r + 1] = lxd;
+}
+
+}  // namespace ears

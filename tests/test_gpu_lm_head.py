@@ -1,0 +1,140 @@
+"""Producer-side fusion on the GPU: the vocabulary projection with the statistics epilogue, against
+the CPU oracle (fp64 dot products, explicit bf16 rounding, three-pass softmax on the emitted rows),
+and the verification step started from the imported statistics."""
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from parity_util import compare
+
+pytestmark = pytest.mark.gpu
+
+NTHREADS = min(16, os.cpu_count() or 1)
+
+
+@pytest.fixture(scope="module")
+def ears():
+    import paper_2512_13194_amd as p
+    p.lib()
+    assert torch.cuda.is_available()
+    return p
+
+
+def _log(msg):
+    print(msg, flush=True)
+
+
+def _bits(t):
+    return t.contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
+
+
+def _val(bits):
+    return (bits.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+
+
+def _operands(N, D, V, seed, sigma=2.5):
+    g = torch.Generator(device="cuda").manual_seed(seed)
+    hidden = torch.randn(N, D, generator=g, device="cuda").to(torch.bfloat16)
+    weight = (torch.randn(V, D, generator=g, device="cuda") * (sigma / D ** 0.5)).to(torch.bfloat16)
+    return hidden, weight
+
+
+def _check_logits(got_bits, exact, want_bits):
+    """Every emitted logit is a bf16 neighbour of the exact sum (fp32 accumulation moves a sum by far
+    less than one bf16 step), and nearly all are the nearest one."""
+    got = _val(got_bits)
+    step = np.maximum(np.abs(exact), 2.0 ** -126) * 2.0 ** -7      # one bf16 step at that magnitude
+    assert (np.abs(got - exact) <= 0.51 * step + 1e-5).all()
+    assert (got_bits == want_bits).mean() > 0.995
+
+
+def _check_stats(oracle, logits_bits, row_max, row_sum, T, rows):
+    for n in rows:
+        Tn = float(T[n]) if isinstance(T, np.ndarray) else float(np.float32(T))
+        _, m, Z, _ = oracle.softmax(logits_bits[n], Tn)
+        assert row_max[n] == m, (n, row_max[n], m)
+        assert abs(row_sum[n] - Z) <= 1e-5 * Z, (n, row_sum[n], Z)
+
+
+@pytest.mark.parametrize("N,D,V", [(1, 64, 1), (70, 128, 1000), (300, 192, 513), (257, 64, 255),
+                                   (33, 256, 2049), (512, 64, 768)])
+def test_projection_and_statistics_small(ears, oracle, N, D, V):
+    _log("lm_head N=%d D=%d V=%d" % (N, D, V))
+    hidden, weight = _operands(N, D, V, seed=N + V)
+    T = 0.8
+    logits, row_max, row_sum = ears.ears_lm_head_bf16(hidden, weight, temperature=T)
+    torch.cuda.synchronize()
+    exact, want = oracle.lm_head(_bits(hidden), _bits(weight), nthreads=NTHREADS)
+    got = _bits(logits)
+    _check_logits(got, exact, want)
+    _check_stats(oracle, got, row_max.cpu().numpy(), row_sum.cpu().numpy(), T, range(N))
+
+
+def test_per_row_temperature(ears, oracle):
+    _log("lm_head per-row temperature")
+    N, D, V = 40, 128, 3000
+    hidden, weight = _operands(N, D, V, seed=5)
+    T = (torch.rand(N, device="cuda") + 0.5).float()
+    logits, row_max, row_sum = ears.ears_lm_head_bf16(hidden, weight, row_temperature=T)
+    torch.cuda.synchronize()
+    _check_stats(oracle, _bits(logits), row_max.cpu().numpy(), row_sum.cpu().numpy(),
+                 T.cpu().numpy(), range(N))
+
+
+def test_verification_from_imported_statistics(ears, oracle):
+    """Target and draft logits come from two projections; their statistics are imported and the
+    step runs DECIDE | SAMPLE only.  Oracle: the whole verification on the emitted logits."""
+    _log("lm_head -> import -> verify")
+    B, K, V, D, T, beta, seed = 12, 3, 5000, 128, 0.9, 0.3, 17
+    ht, wt = _operands(B * (K + 1), D, V, seed=21)
+    g = torch.Generator(device="cuda").manual_seed(22)
+    wd = (wt.float() + 0.08 * torch.randn(V, D, generator=g, device="cuda")).to(torch.bfloat16)
+    hd = ht.view(B, K + 1, D)[:, :K].reshape(B * K, D).contiguous()
+    tl, tm, tz = ears.ears_lm_head_bf16(ht, wt, temperature=T)
+    dl, dm, dz = ears.ears_lm_head_bf16(hd, wd, temperature=T)
+    target, draft = tl.view(B, K + 1, V), dl.view(B, K, V)
+    tokens = torch.multinomial(torch.softmax(draft.float().view(B * K, V) / T, -1), 1,
+                               generator=g).view(B, K).to(torch.int32)
+    ws = torch.empty(ears.ears_workspace_bytes(B * K, B, V), dtype=torch.uint8, device="cuda")
+    ears.ears_import_stats(target, draft, tokens, tm, tz, dm, dz, ws)
+    out = ears.ears_verify_ex(target, draft, tokens, temperature=T, beta=beta, seed=seed, workspace=ws,
+                              stages=ears.EARS_STAGE_DECIDE | ears.EARS_STAGE_SAMPLE,
+                              want_stats=True, want_path=True)
+    torch.cuda.synchronize()
+    ora = oracle.verify(_bits(target), _bits(draft), tokens.cpu().numpy(), float(np.float32(T)),
+                        float(np.float32(beta)), seed, nthreads=NTHREADS)
+    rep = compare(ora, out["accept_len"].cpu().numpy(), out["tokens"].cpu().numpy(),
+                  out["stats"].cpu().numpy(), out["path"].cpu().numpy(), None, K, 2e-3,
+                  tokens.cpu().numpy(), V)
+    assert rep.exempt_decisions == 0 and rep.exempt_tokens == 0
+    assert 0 < ora.accept_len.sum() < B * K
+    # and it is what the unfused call gives on the same logits
+    full = ears.ears_verify_ex(target, draft, tokens, temperature=T, beta=beta, seed=seed)
+    torch.cuda.synchronize()
+    assert torch.equal(full["accept_len"], out["accept_len"]) and torch.equal(full["tokens"], out["tokens"])
+
+
+def test_headline_shape_sampled(ears, oracle):
+    """N = 256 * 9 rows, D = 4096, V = 128256: sampled logits against single fp64 dot products and
+    sampled rows' statistics against the oracle's softmax of the emitted row."""
+    _log("lm_head headline shape")
+    N, D, V, T = 2304, 4096, 128256, 1.0
+    hidden, weight = _operands(N, D, V, seed=1)
+    logits, row_max, row_sum = ears.ears_lm_head_bf16(hidden, weight, temperature=T)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(3)
+    ns = np.concatenate([rng.integers(0, N, 1500), [0, N - 1, 255, 256, 2303]])
+    vs = np.concatenate([rng.integers(0, V, 1500), [0, V - 1, 255, 256, 128255]])
+    hb, wb = _bits(hidden), _bits(weight)
+    got = _val(_bits(logits[torch.as_tensor(ns, device="cuda"), torch.as_tensor(vs, device="cuda")]))
+    exact = np.array([oracle.lm_head_dot(hb, wb, int(n), int(v)) for n, v in zip(ns, vs)])
+    step = np.maximum(np.abs(exact), 2.0 ** -126) * 2.0 ** -7
+    assert (np.abs(got - exact) <= 0.51 * step + 1e-4).all()
+    rows = [0, 1, 255, 256, 1000, 2303]
+    lb = _bits(logits[torch.as_tensor(rows, device="cuda")])
+    rm, rs = row_max.cpu().numpy(), row_sum.cpu().numpy()
+    for i, n in enumerate(rows):
+        _, m, Z, _ = oracle.softmax(lb[i], T)
+        assert rm[n] == m and abs(rs[n] - Z) <= 1e-5 * Z
