@@ -5,10 +5,11 @@
 // registers, and writes the logits once.  The verification step then starts from cached statistics
 // and never re-reads the logits for them.
 //
-// One workgroup (4 waves) computes a 256 (vocabulary) x 256 (tokens) tile; each wave owns 128 x 128
-// as 4 x 4 blocks of v_mfma_f32_32x32x16_bf16 with the vocabulary on the MFMA's row index, so that a
-// lane's 16 accumulator registers of a block are 16 vocabulary entries of ONE token and the
-// statistics start as in-lane reductions.
+// One workgroup (8 waves, two per SIMD) computes a 256 (vocabulary) x 256 (tokens) tile; each wave
+// owns 128 x 64 as 4 x 2 blocks of v_mfma_f32_32x32x16_bf16 (128 accumulator registers, so that two
+// waves fit a SIMD's register file) with the vocabulary on the MFMA's row index: a lane's 16
+// accumulator registers of a block are 16 vocabulary entries of ONE token and the statistics start
+// as in-lane reductions.
 #pragma once
 
 #include "ears_device.h"
@@ -17,11 +18,13 @@ namespace ears {
 
 constexpr int kLmTile = 256;          // tile edge, vocabulary and tokens
 constexpr int kLmBK = 64;             // depth of one staged slab (bf16 elements): 128 bytes per row
-constexpr int kLmThreads = 256;       // 4 waves as 2 (vocabulary) x 2 (tokens)
-constexpr int kLmWaveTile = 128;
-constexpr int kLmSlabBytes = kLmTile * kLmBK * 2;            // 32 KiB per operand per buffer
+constexpr int kLmThreads = 512;       // 8 waves as 2 (vocabulary) x 4 (tokens)
+constexpr int kLmWaveV = 128;         // wave tile along the vocabulary: 4 MFMA blocks
+constexpr int kLmWaveN = 64;          // wave tile along the tokens: 2 MFMA blocks
 constexpr int kLmStageRow = kLmTile * 2 + 8;                 // epilogue staging: 520-byte token rows
-constexpr int kLmSharedBytes = kLmTile * kLmStageRow;        // 133 120 B >= 4 slabs (131 072 B)
+// Four shared arrays: operand A and B of the two slab buffers (32 KiB of each are slab data).  The
+// epilogue reuses them to stage 64 token rows each, hence the 520-byte rows' worth of size.
+constexpr int kLmArrayBytes = 64 * kLmStageRow;              // 33 280 B
 constexpr int kLmPartsPerTile = 2;                           // one partial per wave row of a tile
 
 struct LmHeadProblem {
@@ -50,9 +53,57 @@ __device__ __forceinline__ uint16_t lm_round_bf16(float x) {
   return __builtin_bit_cast(uint16_t, (__bf16)x);  // round to nearest even
 }
 
-__global__ __launch_bounds__(kLmThreads) __attribute__((amdgpu_waves_per_eu(1, 1)))
+// Slab loads go straight from global memory to LDS (16 bytes per lane, lane i of a wave lands at
+// base + 16 i): one instruction fills 8 slab rows.  Wave w, instruction j fills rows 64 j + 8 w ..
+// + 8; lane i supplies the chunk that belongs at position (i & 7) of row (i >> 3) under the swizzle.
+__device__ __forceinline__ void lm_issue_slab(unsigned char* dst, const unsigned char* src,
+                                              const uint32_t (&off)[4], int wave) {
+#pragma unroll
+  for (int j = 0; j < 4; ++j)
+    __builtin_amdgcn_global_load_lds(src + off[j], dst + (64 * j + 8 * wave) * (kLmBK * 2), 16, 0, 0);
+}
+
+// One slab: 4 k-steps of 16; the fragments of the next step are read while the current step's 8
+// MFMAs issue.
+__device__ __forceinline__ void lm_compute_slab(const unsigned char* sA, const unsigned char* sB,
+                                                const int (&fr_off)[4], lm_f32x16 (&acc)[4][2]) {
+  lm_bf16x8 fa[2][4], fb[2][2];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+    fa[0][i] = *reinterpret_cast<const lm_bf16x8*>(sA + fr_off[0] + i * 32 * (kLmBK * 2));
+#pragma unroll
+  for (int j = 0; j < 2; ++j)
+    fb[0][j] = *reinterpret_cast<const lm_bf16x8*>(sB + fr_off[0] + j * 32 * (kLmBK * 2));
+#pragma unroll
+  for (int s = 0; s < 4; ++s) {
+    if (s + 1 < 4) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+        fa[(s + 1) & 1][i] = *reinterpret_cast<const lm_bf16x8*>(sA + fr_off[s + 1] + i * 32 * (kLmBK * 2));
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+        fb[(s + 1) & 1][j] = *reinterpret_cast<const lm_bf16x8*>(sB + fr_off[s + 1] + j * 32 * (kLmBK * 2));
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[s & 1][i], fb[s & 1][j], acc[i][j], 0, 0, 0);
+  }
+}
+
+// all of this wave's direct-to-LDS loads have landed; then every wave's
+__device__ __forceinline__ void lm_slab_ready() {
+  __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0), other counters untouched
+  __syncthreads();
+}
+
+__global__ __launch_bounds__(kLmThreads) __attribute__((amdgpu_waves_per_eu(2, 2)))
 void lm_head_kernel(LmHeadProblem p) {
-  __shared__ __attribute__((aligned(16))) unsigned char smem[kLmSharedBytes];
+  __shared__ __attribute__((aligned(16))) unsigned char s_a0[kLmArrayBytes];
+  __shared__ __attribute__((aligned(16))) unsigned char s_b0[kLmArrayBytes];
+  __shared__ __attribute__((aligned(16))) unsigned char s_a1[kLmArrayBytes];
+  __shared__ __attribute__((aligned(16))) unsigned char s_b1[kLmArrayBytes];
 
   // Workgroup ids go round-robin over the 8 XCDs.  The token tiles that share a vocabulary tile
   // (hence the same weight rows) get consecutive ids on ONE XCD, so the weights reach each L2 once.
@@ -64,100 +115,78 @@ void lm_head_kernel(LmHeadProblem p) {
   const int v0 = vt * kLmTile, n0 = tt * kLmTile;
 
   const int tid = (int)threadIdx.x;
-  const int lane = tid & 63, wave = tid >> 6;
-  const int wv = wave >> 1, wn = wave & 1;  // wave's 128-slice along vocabulary / tokens
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // uniform, and known to be
+  const int wv = wave >> 2, wn = wave & 3;  // wave's 128-slice of the vocabulary / 64-slice of the tokens
 
-  // ---- global -> LDS staging: thread owns chunk (tid & 7) of rows (tid >> 3) + 32 j, j = 0..7 ----
-  const int st_chunk = tid & 7, st_row = tid >> 3;
-  const int st_off = st_row * (kLmBK * 2) + ((st_chunk ^ lm_swizzle(st_row)) << 4);
-  const uint4* gA[8];
-  const uint4* gB[8];
+  // ---- global -> LDS: byte offsets of this lane's chunk in the 4 rows it fetches per operand ----
+  const int ld_row = 8 * wave + (lane >> 3);                       // + 64 j
+  const int ld_chunk = (lane & 7) ^ lm_swizzle(ld_row);            // same for every j
+  uint32_t offA[4], offB[4];
 #pragma unroll
-  for (int j = 0; j < 8; ++j) {
-    int rv = v0 + st_row + 32 * j;
-    int rn = n0 + st_row + 32 * j;
+  for (int j = 0; j < 4; ++j) {
+    int rv = v0 + ld_row + 64 * j;
+    int rn = n0 + ld_row + 64 * j;
     rv = rv < p.V ? rv : p.V - 1;  // rows past the edge re-read the last row; their results are dropped
     rn = rn < p.N ? rn : p.N - 1;
-    gA[j] = reinterpret_cast<const uint4*>(p.weight + (size_t)rv * p.D + st_chunk * 8);
-    gB[j] = reinterpret_cast<const uint4*>(p.hidden + (size_t)rn * p.D + st_chunk * 8);
+    offA[j] = (uint32_t)rv * (uint32_t)(p.D * 2) + (uint32_t)(ld_chunk * 16);
+    offB[j] = (uint32_t)rn * (uint32_t)(p.D * 2) + (uint32_t)(ld_chunk * 16);
   }
+  const unsigned char* gA = reinterpret_cast<const unsigned char*>(p.weight);
+  const unsigned char* gB = reinterpret_cast<const unsigned char*>(p.hidden);
 
   // ---- fragment reads: lane supplies row (lane & 31), k-offset 8 * (lane >> 5) of each block ----
   const int fr_swz = lm_swizzle(lane & 31);
   int fr_off[4];
 #pragma unroll
   for (int s = 0; s < 4; ++s) fr_off[s] = (lane & 31) * (kLmBK * 2) + (((2 * s + (lane >> 5)) ^ fr_swz) << 4);
-  const int fr_A = wv * kLmWaveTile * (kLmBK * 2);
-  const int fr_B = wn * kLmWaveTile * (kLmBK * 2);
+  const int fr_A = wv * kLmWaveV * (kLmBK * 2);
+  const int fr_B = wn * kLmWaveN * (kLmBK * 2);
 
-  lm_f32x16 acc[4][4];
+  lm_f32x16 acc[4][2];
 #pragma unroll
   for (int i = 0; i < 4; ++i)
 #pragma unroll
-    for (int j = 0; j < 4; ++j)
+    for (int j = 0; j < 2; ++j)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
 
+  // Two slab buffers in separate arrays: the loads of slab s + 1 are in flight while slab s is
+  // multiplied; the barrier that ends slab s also says that everyone is done reading it.
   const int n_slabs = p.D / kLmBK;
-  uint4 ra[8], rb[8];
-#pragma unroll
-  for (int j = 0; j < 8; ++j) {
-    ra[j] = *gA[j];
-    rb[j] = *gB[j];
-  }
-#pragma unroll
-  for (int j = 0; j < 8; ++j) {
-    *reinterpret_cast<uint4*>(smem + st_off + j * 32 * (kLmBK * 2)) = ra[j];
-    *reinterpret_cast<uint4*>(smem + kLmSlabBytes + st_off + j * 32 * (kLmBK * 2)) = rb[j];
-  }
-  __syncthreads();
-
-  for (int slab = 0; slab < n_slabs; ++slab) {
-    const int cur = (slab & 1) * 2 * kLmSlabBytes;
-    const int nxt = ((slab + 1) & 1) * 2 * kLmSlabBytes;
-    const bool more = slab + 1 < n_slabs;  // uniform
-    if (more) {
-#pragma unroll
-      for (int j = 0; j < 8; ++j) {
-        ra[j] = *(gA[j] + (size_t)(slab + 1) * (kLmBK / 8));
-        rb[j] = *(gB[j] + (size_t)(slab + 1) * (kLmBK / 8));
-      }
+  const size_t slab_bytes = kLmBK * 2;
+  lm_issue_slab(s_a0, gA, offA, wave);
+  lm_issue_slab(s_b0, gB, offB, wave);
+  lm_slab_ready();
+  for (int slab = 0; slab < n_slabs; slab += 2) {
+    if (slab + 1 < n_slabs) {  // uniform
+      lm_issue_slab(s_a1, gA + (size_t)(slab + 1) * slab_bytes, offA, wave);
+      lm_issue_slab(s_b1, gB + (size_t)(slab + 1) * slab_bytes, offB, wave);
     }
-    const unsigned char* sA = smem + cur + fr_A;
-    const unsigned char* sB = smem + cur + kLmSlabBytes + fr_B;
-#pragma unroll
-    for (int s = 0; s < 4; ++s) {
-      lm_bf16x8 fa[4], fb[4];
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        fa[i] = *reinterpret_cast<const lm_bf16x8*>(sA + fr_off[s] + i * 32 * (kLmBK * 2));
-        fb[i] = *reinterpret_cast<const lm_bf16x8*>(sB + fr_off[s] + i * 32 * (kLmBK * 2));
+    lm_compute_slab(s_a0 + fr_A, s_b0 + fr_B, fr_off, acc);
+    lm_slab_ready();
+    if (slab + 1 < n_slabs) {
+      if (slab + 2 < n_slabs) {
+        lm_issue_slab(s_a0, gA + (size_t)(slab + 2) * slab_bytes, offA, wave);
+        lm_issue_slab(s_b0, gB + (size_t)(slab + 2) * slab_bytes, offB, wave);
       }
-#pragma unroll
-      for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+      lm_compute_slab(s_a1 + fr_A, s_b1 + fr_B, fr_off, acc);
+      lm_slab_ready();
     }
-    if (more) {
-#pragma unroll
-      for (int j = 0; j < 8; ++j) {
-        *reinterpret_cast<uint4*>(smem + nxt + st_off + j * 32 * (kLmBK * 2)) = ra[j];
-        *reinterpret_cast<uint4*>(smem + nxt + kLmSlabBytes + st_off + j * 32 * (kLmBK * 2)) = rb[j];
-      }
-    }
-    __syncthreads();
   }
 
   // ---- epilogue ------------------------------------------------------------------------------
   // acc[i][j][r] is vocabulary entry v0 + wv*128 + i*32 + 8*(r/4) + 4*(lane/32) + r%4 of token
-  // n0 + wn*128 + j*32 + lane%32.  Round, take the statistics of the rounded values, stage the
+  // n0 + wn*64 + j*32 + lane%32.  Round, take the statistics of the rounded values, stage the
   // tile as [token][vocabulary] rows and write them out whole.
   const int half = lane >> 5;
+  // 64 token rows per shared array: the wave's tokens are rows 0..63 of array wn
+  unsigned char* stage_array = wn == 0 ? s_a0 : wn == 1 ? s_b0 : wn == 2 ? s_a1 : s_b1;
 #pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    const int tok_local = wn * kLmWaveTile + j * 32 + (lane & 31);
+  for (int j = 0; j < 2; ++j) {
+    const int tok_local = wn * kLmWaveN + j * 32 + (lane & 31);
     const int tok = n0 + tok_local;
+    unsigned char* stage = stage_array + (j * 32 + (lane & 31)) * kLmStageRow;
     const float T = p.row_T ? p.row_T[tok < p.N ? tok : p.N - 1] : p.T;
     const float c = (float)(kLog2e / (double)T);
     float xr[4][16];
@@ -166,7 +195,7 @@ void lm_head_kernel(LmHeadProblem p) {
     for (int i = 0; i < 4; ++i) {
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
-        const int v_local = wv * kLmWaveTile + i * 32 + 8 * g + 4 * half;
+        const int v_local = wv * kLmWaveV + i * 32 + 8 * g + 4 * half;
         uint16_t b[4];
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
@@ -179,7 +208,7 @@ void lm_head_kernel(LmHeadProblem p) {
         uint2 packed;
         packed.x = (uint32_t)b[0] | ((uint32_t)b[1] << 16);
         packed.y = (uint32_t)b[2] | ((uint32_t)b[3] << 16);
-        *reinterpret_cast<uint2*>(smem + tok_local * kLmStageRow + v_local * 2) = packed;
+        *reinterpret_cast<uint2*>(stage + v_local * 2) = packed;
       }
     }
     // the other half-wave holds the other 64 entries of the same token's 128-slice
@@ -207,7 +236,9 @@ void lm_head_kernel(LmHeadProblem p) {
   for (int row = wave; row < kLmTile; row += kLmThreads / 64) {
     const int tok = n0 + row;
     if (tok >= p.N) break;  // uniform over the wave
-    const uint2 val = *reinterpret_cast<const uint2*>(smem + row * kLmStageRow + lane * 8);
+    const unsigned char* stage_array = (row >> 6) == 0 ? s_a0 : (row >> 6) == 1 ? s_b0
+                                       : (row >> 6) == 2 ? s_a1 : s_b1;
+    const uint2 val = *reinterpret_cast<const uint2*>(stage_array + (row & 63) * kLmStageRow + lane * 8);
     uint16_t* dst = p.logits + (size_t)tok * p.V + v_lane;
     if (v_lane + 3 < p.V && ((reinterpret_cast<uintptr_t>(dst) & 7u) == 0)) {
       *reinterpret_cast<uint2*>(dst) = val;
