@@ -182,6 +182,27 @@ def main() -> int:
                                  "algorithmic_bytes": greedy_bytes,
                                  "achieved_GBps": greedy_bytes / (greedy_ms * 1e-3) / 1e9}}
 
+    # producer-side fusion: the vocabulary projection that emits this batch's target logits
+    # (N = B (K + 1) rows, hidden size 4096) with the statistics epilogue; dense bf16 MFMA peak
+    lm_D = 4096
+    lm_N = B * (K + 1)
+    g = torch.Generator(device="cuda").manual_seed(7)
+    hidden = torch.randn(lm_N, lm_D, generator=g, device="cuda").to(torch.bfloat16)
+    weight = (torch.randn(V, lm_D, generator=g, device="cuda") * (2.5 / lm_D ** 0.5)).to(torch.bfloat16)
+    lm_logits = torch.empty(lm_N, V, dtype=torch.bfloat16, device="cuda")
+    lm_max = torch.empty(lm_N, dtype=torch.float32, device="cuda")
+    lm_sum = torch.empty(lm_N, dtype=torch.float64, device="cuda")
+    lm_ws = torch.empty(ears.ears_lm_head_workspace_bytes(lm_N, V), dtype=torch.uint8, device="cuda")
+    lm_ms = timed_ms(lambda: ears.ears_lm_head_bf16(
+        hidden, weight, temperature=T, out_logits=lm_logits, out_row_max=lm_max,
+        out_row_sumexp=lm_sum, workspace=lm_ws), reps=10)
+    lm_flop = 2.0 * lm_N * lm_D * V
+    other_paths["lm_head_with_statistics"] = {
+        "ms_per_call": lm_ms, "N": lm_N, "D": lm_D, "V": V, "bound": "mfma",
+        "achieved_TFLOPs": lm_flop / (lm_ms * 1e-3) / 1e12, "peak_TFLOPs": 2500.0,
+        "frac": lm_flop / (lm_ms * 1e-3) / 1e12 / 2500.0}
+    del hidden, weight, lm_ws, lm_logits
+
     if args.traffic_calibration:
         # plain copy of the draft buffer: reads and writes exactly draft.numel() * 2 bytes
         dst = torch.empty_like(batch.draft)

@@ -25,6 +25,8 @@ constexpr int kLmStageRow = kLmTile * 2 + 8;                 // epilogue staging
 // Four shared arrays: operand A and B of the two slab buffers (32 KiB of each are slab data).  The
 // epilogue reuses them to stage 64 token rows each, hence the 520-byte rows' worth of size.
 constexpr int kLmArrayBytes = 64 * kLmStageRow;              // 33 280 B
+constexpr int kLmWeightPolicy = 2;    // weights stream through once per XCD: non-temporal
+constexpr int kLmHiddenPolicy = 0;    // hidden states are re-read by every vocabulary tile
 constexpr int kLmPartsPerTile = 2;                           // one partial per wave row of a tile
 
 struct LmHeadProblem {
@@ -56,39 +58,45 @@ __device__ __forceinline__ uint16_t lm_round_bf16(float x) {
 // Slab loads go straight from global memory to LDS (16 bytes per lane, lane i of a wave lands at
 // base + 16 i): one instruction fills 8 slab rows.  Wave w, instruction j fills rows 64 j + 8 w ..
 // + 8; lane i supplies the chunk that belongs at position (i & 7) of row (i >> 3) under the swizzle.
+// kAux is the cache-policy operand of the load: 0 default, 2 non-temporal.
+template <int kAux>
 __device__ __forceinline__ void lm_issue_slab(unsigned char* dst, const unsigned char* src,
                                               const uint32_t (&off)[4], int wave) {
 #pragma unroll
   for (int j = 0; j < 4; ++j)
-    __builtin_amdgcn_global_load_lds(src + off[j], dst + (64 * j + 8 * wave) * (kLmBK * 2), 16, 0, 0);
+    __builtin_amdgcn_global_load_lds(src + off[j], dst + (64 * j + 8 * wave) * (kLmBK * 2), 16, 0, kAux);
 }
 
-// One slab: 4 k-steps of 16; the fragments of the next step are read while the current step's 8
-// MFMAs issue.
-__device__ __forceinline__ void lm_compute_slab(const unsigned char* sA, const unsigned char* sB,
-                                                const int (&fr_off)[4], lm_f32x16 (&acc)[4][2]) {
-  lm_bf16x8 fa[2][4], fb[2][2];
+// Fragments of one k-step: 4 blocks of vocabulary rows (A) and 2 blocks of token rows (B).
+struct LmFrags {
+  lm_bf16x8 a[4], b[2];
+};
+__device__ __forceinline__ void lm_read_frags(LmFrags& f, const unsigned char* sA,
+                                              const unsigned char* sB, int off) {
 #pragma unroll
   for (int i = 0; i < 4; ++i)
-    fa[0][i] = *reinterpret_cast<const lm_bf16x8*>(sA + fr_off[0] + i * 32 * (kLmBK * 2));
+    f.a[i] = *reinterpret_cast<const lm_bf16x8*>(sA + off + i * 32 * (kLmBK * 2));
 #pragma unroll
   for (int j = 0; j < 2; ++j)
-    fb[0][j] = *reinterpret_cast<const lm_bf16x8*>(sB + fr_off[0] + j * 32 * (kLmBK * 2));
+    f.b[j] = *reinterpret_cast<const lm_bf16x8*>(sB + off + j * 32 * (kLmBK * 2));
+}
+
+// One slab: 4 k-steps of 16.  `f0` already holds the fragments of step 0; the fragments of the next
+// step are read while the current step's 8 MFMAs issue.
+__device__ __forceinline__ void lm_compute_slab(LmFrags& f0, const unsigned char* sA,
+                                                const unsigned char* sB, const int (&fr_off)[4],
+                                                lm_f32x16 (&acc)[4][2]) {
+  LmFrags f1;
 #pragma unroll
   for (int s = 0; s < 4; ++s) {
-    if (s + 1 < 4) {
-#pragma unroll
-      for (int i = 0; i < 4; ++i)
-        fa[(s + 1) & 1][i] = *reinterpret_cast<const lm_bf16x8*>(sA + fr_off[s + 1] + i * 32 * (kLmBK * 2));
-#pragma unroll
-      for (int j = 0; j < 2; ++j)
-        fb[(s + 1) & 1][j] = *reinterpret_cast<const lm_bf16x8*>(sB + fr_off[s + 1] + j * 32 * (kLmBK * 2));
-    }
+    LmFrags& cur = (s & 1) ? f1 : f0;
+    LmFrags& nxt = (s & 1) ? f0 : f1;
+    if (s + 1 < 4) lm_read_frags(nxt, sA, sB, fr_off[s + 1]);
 #pragma unroll
     for (int i = 0; i < 4; ++i)
 #pragma unroll
       for (int j = 0; j < 2; ++j)
-        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[s & 1][i], fb[s & 1][j], acc[i][j], 0, 0, 0);
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur.a[i], cur.b[j], acc[i][j], 0, 0, 0);
   }
 }
 
@@ -155,22 +163,26 @@ void lm_head_kernel(LmHeadProblem p) {
   // multiplied; the barrier that ends slab s also says that everyone is done reading it.
   const int n_slabs = p.D / kLmBK;
   const size_t slab_bytes = kLmBK * 2;
-  lm_issue_slab(s_a0, gA, offA, wave);
-  lm_issue_slab(s_b0, gB, offB, wave);
+  lm_issue_slab<kLmWeightPolicy>(s_a0, gA, offA, wave);
+  lm_issue_slab<kLmHiddenPolicy>(s_b0, gB, offB, wave);
   lm_slab_ready();
+  LmFrags f0;
   for (int slab = 0; slab < n_slabs; slab += 2) {
+    // the first fragments of the slab are asked for before the next slab's loads are issued
+    lm_read_frags(f0, s_a0 + fr_A, s_b0 + fr_B, fr_off[0]);
     if (slab + 1 < n_slabs) {  // uniform
-      lm_issue_slab(s_a1, gA + (size_t)(slab + 1) * slab_bytes, offA, wave);
-      lm_issue_slab(s_b1, gB + (size_t)(slab + 1) * slab_bytes, offB, wave);
+      lm_issue_slab<kLmWeightPolicy>(s_a1, gA + (size_t)(slab + 1) * slab_bytes, offA, wave);
+      lm_issue_slab<kLmHiddenPolicy>(s_b1, gB + (size_t)(slab + 1) * slab_bytes, offB, wave);
     }
-    lm_compute_slab(s_a0 + fr_A, s_b0 + fr_B, fr_off, acc);
+    lm_compute_slab(f0, s_a0 + fr_A, s_b0 + fr_B, fr_off, acc);
     lm_slab_ready();
     if (slab + 1 < n_slabs) {
+      lm_read_frags(f0, s_a1 + fr_A, s_b1 + fr_B, fr_off[0]);
       if (slab + 2 < n_slabs) {
-        lm_issue_slab(s_a0, gA + (size_t)(slab + 2) * slab_bytes, offA, wave);
-        lm_issue_slab(s_b0, gB + (size_t)(slab + 2) * slab_bytes, offB, wave);
+        lm_issue_slab<kLmWeightPolicy>(s_a0, gA + (size_t)(slab + 2) * slab_bytes, offA, wave);
+        lm_issue_slab<kLmHiddenPolicy>(s_b0, gB + (size_t)(slab + 2) * slab_bytes, offB, wave);
       }
-      lm_compute_slab(s_a1 + fr_A, s_b1 + fr_B, fr_off, acc);
+      lm_compute_slab(f0, s_a1 + fr_A, s_b1 + fr_B, fr_off, acc);
       lm_slab_ready();
     }
   }

@@ -164,3 +164,45 @@ def test_greedy_argument_errors(L):
     assert _greedy(L, off=P + 4) == b.EARS_ERR_ALIGN
     assert _greedy(L, ws=P + 16) == b.EARS_ERR_ALIGN
     assert _greedy(L, wsb=16) == b.EARS_ERR_WORKSPACE
+
+
+def _lm(L, hidden=P, weight=P, N=8, D=128, V=100, T=1.0, rowT=None, logits=P, rmax=P, rsum=P,
+        ws=P, wsb=1 << 20):
+    return L.ears_lm_head_bf16(hidden, weight, N, D, V, T, rowT, logits, rmax, rsum, ws, wsb, None)
+
+
+def test_lm_head_argument_errors(L):
+    from paper_2512_13194_amd import binding as b
+    w = b.ears_lm_head_workspace_bytes(2304, 128256)
+    assert w >= 2 * 2304 * 2 * 501 * 4 and w % 256 == 0
+    assert b.ears_lm_head_workspace_bytes(0, 5) == 0 and b.ears_lm_head_workspace_bytes(5, 0) == 0
+    for name in ("hidden", "weight", "logits", "rmax", "rsum"):
+        assert _lm(L, **{name: None}) == b.EARS_ERR_NULL
+    assert _lm(L, N=0) == b.EARS_ERR_SHAPE
+    assert _lm(L, V=0) == b.EARS_ERR_SHAPE
+    assert _lm(L, D=96) == b.EARS_ERR_SHAPE               # D must be a multiple of 64
+    assert _lm(L, D=0) == b.EARS_ERR_SHAPE
+    assert _lm(L, N=1 << 16, V=1 << 16) == b.EARS_ERR_SHAPE  # N * V >= 2^31
+    assert _lm(L, V=1 << 20, D=4096) == b.EARS_ERR_SHAPE      # weight beyond 32-bit byte offsets
+    assert _lm(L, T=0.0) == b.EARS_ERR_PARAM
+    assert _lm(L, T=float("nan")) == b.EARS_ERR_PARAM
+    assert _lm(L, hidden=P + 8) == b.EARS_ERR_ALIGN
+    assert _lm(L, rsum=P + 4) == b.EARS_ERR_ALIGN
+    assert _lm(L, ws=None) == b.EARS_ERR_WORKSPACE
+    assert _lm(L, wsb=64) == b.EARS_ERR_WORKSPACE
+    assert _lm(L, ws=P + 64) == b.EARS_ERR_ALIGN
+
+
+def test_import_stats_argument_errors(L):
+    from paper_2512_13194_amd import binding as b
+
+    def imp(dtype=1, target=P, draft=P, tokens=P, off=None, R=6, B=2, K=3, V=64, tm=P, ts=P, dm=P,
+            ds=P, ws=P, wsb=1 << 20):
+        return L.ears_import_stats(dtype, target, draft, tokens, off, R, B, K, V, tm, ts, dm, ds, ws,
+                                   wsb, None)
+    for name in ("tm", "ts", "dm", "ds", "target", "draft", "tokens"):
+        assert imp(**{name: None}) == b.EARS_ERR_NULL
+    assert imp(dtype=3) == b.EARS_ERR_DTYPE
+    assert imp(R=7) == b.EARS_ERR_SHAPE
+    assert imp(ts=P + 4) == b.EARS_ERR_ALIGN
+    assert imp(wsb=8) == b.EARS_ERR_WORKSPACE
