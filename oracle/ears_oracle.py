@@ -16,6 +16,8 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "ears_oracle.c")
 _LIB = os.path.join(_HERE, "libears_oracle.so")
+# The mutation tests point this at a deliberately broken build to show that the pins catch it.
+_LIB_OVERRIDE = os.environ.get("EARS_ORACLE_LIB")
 
 NDIAG = 10
 NSAMP = 4
@@ -41,8 +43,11 @@ def _load():
     global _lib
     if _lib is not None:
         return _lib
-    build()
-    lib = ctypes.CDLL(_LIB)
+    if _LIB_OVERRIDE:
+        lib = ctypes.CDLL(_LIB_OVERRIDE)
+    else:
+        build()
+        lib = ctypes.CDLL(_LIB)
     c = ctypes
     u32p = c.POINTER(c.c_uint32)
     lib.ears_oracle_philox4x32_10.argtypes = [u32p, u32p, u32p]

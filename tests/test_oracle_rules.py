@@ -145,6 +145,21 @@ def test_division_guard(oracle):
     assert r.d("R")[0, 0] < 0.02
 
 
+def test_comparison_is_not_strict(oracle):
+    # Section 3.2 step 5 compares with >=.  With beta = 2 and a target that is uniform over two
+    # entries (uncertainty 1/2) the tolerance is 1, so the clamped threshold is exactly 0 for every
+    # U, and a draft token the target gives probability 0 (R = 0) is still accepted: 0 >= 0.
+    T = 1.0
+    lt = np.array([0.0, 0.0, -np.inf, -np.inf], dtype=np.float32)
+    ld = logits_from_probs([0.25] * 4, T)
+    target = np.stack([lt] * 2)[None]
+    draft = ld[None, None]
+    for seed in range(5):
+        r = oracle.verify(target, draft, np.array([[2]], dtype=np.int32), T, 2.0, seed)
+        assert r.d("R")[0, 0] == 0.0 and r.d("thr")[0, 0] == 0.0
+        assert r.path[0, 0] == 2 and r.accept_len[0] == 1
+
+
 def test_out_of_range_token_is_rejected(oracle):
     T = 1.0
     lt = logits_from_probs([0.25] * 4, T)
