@@ -189,6 +189,9 @@ def test_seq_ids_batch_order_invariance_and_determinism(ears, oracle):
                                seed=12, seq_ids=torch.as_tensor(ids, device="cuda"))
     torch.cuda.synchronize()
     assert torch.equal(out2["tokens"], out["tokens"]) and torch.equal(out2["accept_len"], out["accept_len"])
+    # a seed with high bits set: both halves of the Philox key are in use
+    rep, _, _ = run_rect(ears, oracle, batch, 1.0, 0.25, 0xDEADBEEF12345678, seq_ids=ids)
+    assert rep.exempt_decisions == 0 and rep.exempt_tokens == 0
     perm = torch.randperm(40, generator=torch.Generator().manual_seed(3)).cuda()
     out3 = ears.ears_verify_ex(batch.target[perm].contiguous(), batch.draft[perm].contiguous(),
                                batch.tokens[perm].contiguous(), temperature=1.0, beta=0.25, seed=12,
