@@ -14,13 +14,14 @@ namespace ears {
 // of R or the threshold.  Returns 0 reject, 1 accepted by R >= U, 2 accepted only through the
 // tolerance (1 for either kind of acceptance when neither statistics nor branch ids are asked
 // for).  Writes the optional per-position statistics / branch id and raises the status bit for
-// an invalid token.
-__device__ __forceinline__ int decide_position(const Problem& p, int b, int i, int64_t r, double mt,
-                                               double Zt, double lxt, double md, double Zd,
-                                               double lxd, double unc) {
+// an invalid token.  x is the draft token and U the acceptance uniform of the position (step 3):
+// the caller fetches and draws them ahead of time, so that nothing slow is left for the moment the
+// statistics arrive.
+__device__ __forceinline__ int decide_position(const Problem& p, int b, int64_t r, int32_t x,
+                                               double U, double mt, double Zt, double lxt,
+                                               double md, double Zd, double lxd, double unc) {
   const double T = (double)seq_temperature(p, b);
   const double beta = (double)seq_beta(p, b);
-  const int32_t x = p.tokens[r];
   const bool valid = x >= 0 && x < p.V;
   if (valid && !p.out_stats && !p.out_path) {
     // Most decisions are far from the threshold: settle those in fp32 with a margin that covers
@@ -31,7 +32,7 @@ __device__ __forceinline__ int decide_position(const Problem& p, int b, int i, i
     const float Pdf = __builtin_amdgcn_exp2f(((float)lxd - (float)md) * cf) / (float)Zd;
     if (Pdf > 1e-9f) {
       const float Rf = Ptf / Pdf;
-      const float Uf = (float)accept_uniform(p.seed, seq_rng_id(p, b), (uint32_t)i);
+      const float Uf = (float)U;  // 24 bits: exact
       const float thrf = fmaxf(Uf - (float)beta * (float)unc, 0.0f);
       const float slack = 1e-6f * (1.0f + (float)beta);
       if (Rf * (1.0f - 1e-4f) > thrf + slack) return 1;
@@ -41,7 +42,6 @@ __device__ __forceinline__ int decide_position(const Problem& p, int b, int i, i
   const double Ptx = valid ? exp((lxt - mt) / T) / Zt : 0.0;
   const double Pdx = valid ? exp((lxd - md) / T) / Zd : 0.0;
   const double R = Ptx / fmax(Pdx, kEpsilon);                              // step 2, division guard
-  const double U = accept_uniform(p.seed, seq_rng_id(p, b), (uint32_t)i);  // step 3
   const double tol = beta * unc;                          // step 4
   const double thr = fmax(U - tol, 0.0);                  // threshold clamp
   int decision;                                           // step 5
@@ -81,9 +81,10 @@ __device__ __forceinline__ int first_reject_scan(const Problem& p, int b, int la
       } else {
         const double Zt = p.Z[2 * r];
         const double unc = p.unc_mode ? p.unc[r] : 1.0 - 1.0 / Zt;  // max P_t = 1/Z_t
-        decision = decide_position(p, b, i, r, (double)p.m[2 * r], Zt, (double)p.lx[2 * r],
-                                   (double)p.m[2 * r + 1], p.Z[2 * r + 1], (double)p.lx[2 * r + 1],
-                                   unc);
+        const double U = accept_uniform(p.seed, seq_rng_id(p, b), (uint32_t)i);
+        decision = decide_position(p, b, r, p.tokens[r], U, (double)p.m[2 * r], Zt,
+                                   (double)p.lx[2 * r], (double)p.m[2 * r + 1], p.Z[2 * r + 1],
+                                   (double)p.lx[2 * r + 1], unc);
         p.decisions[r] = decision;
       }
     }

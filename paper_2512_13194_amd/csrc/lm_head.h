@@ -58,13 +58,18 @@ __device__ __forceinline__ uint16_t lm_round_bf16(float x) {
 // Slab loads go straight from global memory to LDS (16 bytes per lane, lane i of a wave lands at
 // base + 16 i): one instruction fills 8 slab rows.  Wave w, instruction j fills rows 64 j + 8 w ..
 // + 8; lane i supplies the chunk that belongs at position (i & 7) of row (i >> 3) under the swizzle.
-// kAux is the cache-policy operand of the load: 0 default, 2 non-temporal.
+// Buffer addressing: the operand is a raw buffer (base and byte size in a scalar descriptor), a lane
+// adds its own 32-bit byte offset and the instruction a scalar one (slab and row block), so the
+// loop needs no address arithmetic; rows past the end of the matrix fall outside the buffer and
+// read as zero.  kAux is the cache-policy operand of the load: 0 default, 2 non-temporal.
 template <int kAux>
-__device__ __forceinline__ void lm_issue_slab(unsigned char* dst, const unsigned char* src,
-                                              const uint32_t (&off)[4], int wave) {
+__device__ __forceinline__ void lm_issue_slab(unsigned char* dst, __amdgpu_buffer_rsrc_t rsrc,
+                                              uint32_t lane_off, uint32_t slab_off,
+                                              uint32_t block_stride, int wave) {
 #pragma unroll
   for (int j = 0; j < 4; ++j)
-    __builtin_amdgcn_global_load_lds(src + off[j], dst + (64 * j + 8 * wave) * (kLmBK * 2), 16, 0, kAux);
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, dst + (64 * j + 8 * wave) * (kLmBK * 2), 16,
+                                             lane_off, slab_off + (uint32_t)j * block_stride, 0, kAux);
 }
 
 // Fragments of one k-step: 4 blocks of vocabulary rows (A) and 2 blocks of token rows (B).
@@ -127,21 +132,18 @@ void lm_head_kernel(LmHeadProblem p) {
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // uniform, and known to be
   const int wv = wave >> 2, wn = wave & 3;  // wave's 128-slice of the vocabulary / 64-slice of the tokens
 
-  // ---- global -> LDS: byte offsets of this lane's chunk in the 4 rows it fetches per operand ----
-  const int ld_row = 8 * wave + (lane >> 3);                       // + 64 j
-  const int ld_chunk = (lane & 7) ^ lm_swizzle(ld_row);            // same for every j
-  uint32_t offA[4], offB[4];
-#pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    int rv = v0 + ld_row + 64 * j;
-    int rn = n0 + ld_row + 64 * j;
-    rv = rv < p.V ? rv : p.V - 1;  // rows past the edge re-read the last row; their results are dropped
-    rn = rn < p.N ? rn : p.N - 1;
-    offA[j] = (uint32_t)rv * (uint32_t)(p.D * 2) + (uint32_t)(ld_chunk * 16);
-    offB[j] = (uint32_t)rn * (uint32_t)(p.D * 2) + (uint32_t)(ld_chunk * 16);
-  }
-  const unsigned char* gA = reinterpret_cast<const unsigned char*>(p.weight);
-  const unsigned char* gB = reinterpret_cast<const unsigned char*>(p.hidden);
+  // ---- global -> LDS: this lane's chunk of rows ld_row + 64 j of both operands ----
+  const int ld_row = 8 * wave + (lane >> 3);
+  const uint32_t ld_chunk_off = (uint32_t)(((lane & 7) ^ lm_swizzle(ld_row)) * 16);
+  const uint32_t row_bytes = (uint32_t)(p.D * 2);
+  const uint32_t block_stride = 64u * row_bytes;
+  const uint32_t offA = (uint32_t)(v0 + ld_row) * row_bytes + ld_chunk_off;
+  const uint32_t offB = (uint32_t)(n0 + ld_row) * row_bytes + ld_chunk_off;
+  // raw buffer descriptors (stride 0, 32-bit data format): sizes are checked on the host to fit 32 bits
+  const __amdgpu_buffer_rsrc_t rA = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<uint16_t*>(p.weight), 0, (int)((uint32_t)p.V * row_bytes), 0x00020000);
+  const __amdgpu_buffer_rsrc_t rB = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<uint16_t*>(p.hidden), 0, (int)((uint32_t)p.N * row_bytes), 0x00020000);
 
   // ---- fragment reads: lane supplies row (lane & 31), k-offset 8 * (lane >> 5) of each block ----
   const int fr_swz = lm_swizzle(lane & 31);
@@ -162,25 +164,25 @@ void lm_head_kernel(LmHeadProblem p) {
   // Two slab buffers in separate arrays: the loads of slab s + 1 are in flight while slab s is
   // multiplied; the barrier that ends slab s also says that everyone is done reading it.
   const int n_slabs = p.D / kLmBK;
-  const size_t slab_bytes = kLmBK * 2;
-  lm_issue_slab<kLmWeightPolicy>(s_a0, gA, offA, wave);
-  lm_issue_slab<kLmHiddenPolicy>(s_b0, gB, offB, wave);
+  const uint32_t slab_bytes = kLmBK * 2;
+  lm_issue_slab<kLmWeightPolicy>(s_a0, rA, offA, 0u, block_stride, wave);
+  lm_issue_slab<kLmHiddenPolicy>(s_b0, rB, offB, 0u, block_stride, wave);
   lm_slab_ready();
   LmFrags f0;
   for (int slab = 0; slab < n_slabs; slab += 2) {
     // the first fragments of the slab are asked for before the next slab's loads are issued
     lm_read_frags(f0, s_a0 + fr_A, s_b0 + fr_B, fr_off[0]);
     if (slab + 1 < n_slabs) {  // uniform
-      lm_issue_slab<kLmWeightPolicy>(s_a1, gA + (size_t)(slab + 1) * slab_bytes, offA, wave);
-      lm_issue_slab<kLmHiddenPolicy>(s_b1, gB + (size_t)(slab + 1) * slab_bytes, offB, wave);
+      lm_issue_slab<kLmWeightPolicy>(s_a1, rA, offA, (uint32_t)(slab + 1) * slab_bytes, block_stride, wave);
+      lm_issue_slab<kLmHiddenPolicy>(s_b1, rB, offB, (uint32_t)(slab + 1) * slab_bytes, block_stride, wave);
     }
     lm_compute_slab(f0, s_a0 + fr_A, s_b0 + fr_B, fr_off, acc);
     lm_slab_ready();
     if (slab + 1 < n_slabs) {
       lm_read_frags(f0, s_a1 + fr_A, s_b1 + fr_B, fr_off[0]);
       if (slab + 2 < n_slabs) {
-        lm_issue_slab<kLmWeightPolicy>(s_a0, gA + (size_t)(slab + 2) * slab_bytes, offA, wave);
-        lm_issue_slab<kLmHiddenPolicy>(s_b0, gB + (size_t)(slab + 2) * slab_bytes, offB, wave);
+        lm_issue_slab<kLmWeightPolicy>(s_a0, rA, offA, (uint32_t)(slab + 2) * slab_bytes, block_stride, wave);
+        lm_issue_slab<kLmHiddenPolicy>(s_b0, rB, offB, (uint32_t)(slab + 2) * slab_bytes, block_stride, wave);
       }
       lm_compute_slab(f0, s_a1 + fr_A, s_b1 + fr_B, fr_off, acc);
       lm_slab_ready();

@@ -152,14 +152,19 @@ __global__ __launch_bounds__(kBlock) void row_stats_kernel(Problem p) {
   const storage* trow = static_cast<const storage*>(p.target) + (r + b) * (int64_t)V;
   const storage* drow = static_cast<const storage*>(p.draft) + r * (int64_t)V;
 
-  // the draft token's two logits are fetched first so that they arrive while the rows stream
+  // the draft token's two logits are fetched first so that they arrive while the rows stream,
+  // and the position's acceptance uniform is drawn while they do
   float lxt = -INFINITY, lxd = -INFINITY;
+  int32_t x = -1;
+  double U = 0.0;
   if (threadIdx.x == 0) {
-    const int32_t x = p.tokens[r];
+    x = p.tokens[r];
     if (x >= 0 && x < V) {
       lxt = DT::load(trow, x);
       lxd = DT::load(drow, x);
     }
+    if (kDecide)
+      U = accept_uniform(p.seed, seq_rng_id(p, b), (uint32_t)(r - seq_row_begin(p, b)));
   }
 
   float Mt = 0.0f, Md = 0.0f;
@@ -180,11 +185,9 @@ __global__ __launch_bounds__(kBlock) void row_stats_kernel(Problem p) {
       unc = V > 1 ? fmin(fmax(Ht / log((double)V), 0.0), 1.0) : 0.0;
       p.unc[r] = unc;
     }
-    if (kDecide) {
-      const int i = (int)(r - seq_row_begin(p, b));
-      p.decisions[r] = decide_position(p, b, i, r, (double)Mt, Zt, (double)lxt, (double)Md, Zd,
+    if (kDecide)
+      p.decisions[r] = decide_position(p, b, r, x, U, (double)Mt, Zt, (double)lxt, (double)Md, Zd,
                                        (double)lxd, unc);
-    }
   }
 }
 
