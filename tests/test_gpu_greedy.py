@@ -40,7 +40,8 @@ def _check_rect(ears, oracle, target, tokens):
     (1, 1, 1, torch.float32), (3, 2, 8, torch.float32), (5, 3, 13, torch.bfloat16),
     (4, 1, 1003, torch.bfloat16), (2, 4, 4099, torch.float32), (7, 8, 8192, torch.bfloat16),
     (3, 2, 8200, torch.bfloat16), (2, 3, 65537, torch.bfloat16), (33, 5, 2048, torch.float32),
-    (300, 2, 520, torch.bfloat16), (64, 5, 32000, torch.bfloat16),
+    (300, 2, 520, torch.bfloat16), (64, 5, 32000, torch.bfloat16), (2000, 1, 50, torch.float32),
+    (3, 70, 300, torch.bfloat16), (2, 130, 64, torch.float32), (2, 2, 300001, torch.bfloat16),
 ])
 def test_greedy_shapes(ears, oracle, B, K, V, dtype):
     from paper_2512_13194_amd import inputs
