@@ -218,6 +218,16 @@ int ears_lm_head_bf16(const void* hidden, const void* weight, int N, int D, int 
                       float* out_row_max, double* out_row_sumexp, void* workspace,
                       size_t workspace_bytes, void* stream);
 
+/* The same per-row statistics for logits that already exist: one streaming pass over the rows of
+ * ONE matrix, [rows, V] row-major (16-byte aligned base), at temperature T (scalar, or per row when
+ * row_temperature is not NULL).  A pipeline can run it on the draft logits as soon as the draft
+ * model has produced them, and on the target logits after the target pass ("pre-computation",
+ * Section 3.3 item 1), and hand both to ears_import_stats().
+ *   out_row_max [rows] float, out_row_sumexp [rows] double */
+int ears_row_stats(int dtype, const void* logits, int64_t rows, int V, float temperature,
+                   const float* row_temperature, float* out_row_max, double* out_row_sumexp,
+                   void* stream);
+
 /* Fills the statistics part of a verification workspace from per-row statistics computed by the
  * producers of the logits (ears_lm_head_bf16 for the target and for the draft model), and gathers
  * the draft tokens' logits.  Afterwards ears_verify_ex with stages DECIDE | SAMPLE (same batch,

@@ -25,6 +25,7 @@ from .binding import (  # noqa: F401
     ears_lm_head_bf16,
     ears_lm_head_workspace_bytes,
     ears_release,
+    ears_row_stats,
     ears_verify_bf16,
     ears_verify_ex,
     ears_verify_f32,

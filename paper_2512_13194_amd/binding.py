@@ -67,6 +67,8 @@ def lib() -> ctypes.CDLL:
         L.ears_lm_head_workspace_bytes.restype = sz
         L.ears_lm_head_bf16.argtypes = [vp, vp, i32, i32, i32, f32, vp, vp, vp, vp, vp, sz, vp]
         L.ears_lm_head_bf16.restype = i32
+        L.ears_row_stats.argtypes = [i32, vp, i64, i32, f32, vp, vp, vp, vp]
+        L.ears_row_stats.restype = i32
         L.ears_import_stats.argtypes = [i32, vp, vp, vp, vp, i64, i32, i32, i32, vp, vp, vp, vp, vp,
                                         sz, vp]
         L.ears_import_stats.restype = i32
@@ -300,6 +302,30 @@ def ears_lm_head_bf16(hidden, weight, *, temperature=1.0, row_temperature=None, 
                                    _ptr(out_row_sumexp), _ptr(workspace), workspace.numel(),
                                    _stream(stream)))
     return out_logits, out_row_max, out_row_sumexp
+
+
+def ears_row_stats(logits, *, temperature=1.0, row_temperature=None, out_row_max=None,
+                   out_row_sumexp=None, stream=None):
+    """Per-row (max, sum-exp) of logits [..., V] (f32 or bf16): returns (row_max f32, row_sumexp f64)
+    shaped like the leading dimensions."""
+    _need(logits, logits.dtype, "logits")
+    V = logits.shape[-1]
+    rows = logits.numel() // V
+    lead = tuple(logits.shape[:-1])
+    if out_row_max is None:
+        out_row_max = torch.empty(lead, dtype=torch.float32, device=logits.device)
+    if out_row_sumexp is None:
+        out_row_sumexp = torch.empty(lead, dtype=torch.float64, device=logits.device)
+    _need(out_row_max, torch.float32, "out_row_max")
+    _need(out_row_sumexp, torch.float64, "out_row_sumexp")
+    assert out_row_max.numel() == rows == out_row_sumexp.numel()
+    if row_temperature is not None:
+        _need(row_temperature, torch.float32, "row_temperature")
+        assert row_temperature.numel() == rows
+    _check(lib().ears_row_stats(_dtype_code(logits), _ptr(logits), rows, V, float(temperature),
+                                _ptr(row_temperature), _ptr(out_row_max), _ptr(out_row_sumexp),
+                                _stream(stream)))
+    return out_row_max, out_row_sumexp
 
 
 def ears_import_stats(target_logits, draft_logits, draft_tokens, target_row_max, target_row_sumexp,

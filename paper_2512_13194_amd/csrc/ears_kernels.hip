@@ -414,6 +414,32 @@ int ears_lm_head_bf16(const void* hidden, const void* weight, int N, int D, int 
   return hipGetLastError() == hipSuccess ? EARS_OK : EARS_ERR_HIP;
 }
 
+int ears_row_stats(int dtype, const void* logits, int64_t rows, int V, float temperature,
+                   const float* row_temperature, float* out_row_max, double* out_row_sumexp,
+                   void* stream) {
+  if (dtype != EARS_F32 && dtype != EARS_BF16) return EARS_ERR_DTYPE;
+  if (!logits || !out_row_max || !out_row_sumexp) return EARS_ERR_NULL;
+  if (rows < 1 || rows > (int64_t)0x7FFFFFFF || V < 1) return EARS_ERR_SHAPE;
+  if (!row_temperature && !(std::isfinite(temperature) && temperature > 0.0f)) return EARS_ERR_PARAM;
+  if (!aligned(logits, 16) || !aligned(out_row_max, 4) || !aligned(out_row_sumexp, 8) ||
+      !aligned(row_temperature, 4))
+    return EARS_ERR_ALIGN;
+  RowStatsProblem p;
+  p.logits = logits;
+  p.rows = rows;
+  p.V = V;
+  p.T = temperature;
+  p.row_T = row_temperature;
+  p.row_m = out_row_max;
+  p.row_Z = out_row_sumexp;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if (dtype == EARS_F32)
+    hipLaunchKernelGGL((single_row_stats_kernel<F32, 4>), dim3((unsigned)rows), dim3(kBlock), 0, s, p);
+  else
+    hipLaunchKernelGGL((single_row_stats_kernel<BF16, 4>), dim3((unsigned)rows), dim3(kBlock), 0, s, p);
+  return hipGetLastError() == hipSuccess ? EARS_OK : EARS_ERR_HIP;
+}
+
 int ears_import_stats(int dtype, const void* target_logits, const void* draft_logits,
                       const int32_t* draft_tokens, const int64_t* row_offsets,
                       int64_t total_draft_rows, int B, int K, int V, const float* target_row_max,

@@ -191,4 +191,34 @@ __global__ __launch_bounds__(kBlock) void row_stats_kernel(Problem p) {
   }
 }
 
+// Statistics of the rows of ONE matrix (the target's or the draft's logits on their own): what a
+// pipeline runs right after the model that produced them, ahead of the verification step.
+struct RowStatsProblem {
+  const void* logits;  // [rows, V]
+  int64_t rows;
+  int V;
+  float T;
+  const float* row_T;  // [rows] or nullptr
+  float* row_m;        // [rows]
+  double* row_Z;       // [rows]
+};
+
+template <typename DT, int kUnroll>
+__global__ __launch_bounds__(kBlock) void single_row_stats_kernel(RowStatsProblem p) {
+  using storage = typename DT::storage;
+  __shared__ float sh_m[kWavesPerBlock];
+  __shared__ double sh_s[2 * kWavesPerBlock];
+  const int64_t row = (int64_t)blockIdx.x;
+  const float T = p.row_T ? p.row_T[row] : p.T;
+  const float c = (float)(kLog2e / (double)T);
+  float M = 0.0f;
+  double Z = 0.0, H = 0.0;
+  row_pass<DT, kUnroll, false>(static_cast<const storage*>(p.logits) + row * (int64_t)p.V, p.V, c,
+                               sh_m, sh_s, M, Z, H);
+  if (threadIdx.x == 0) {
+    p.row_m[row] = M;
+    p.row_Z[row] = Z;
+  }
+}
+
 }  // namespace ears

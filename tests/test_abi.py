@@ -207,3 +207,15 @@ def test_import_stats_argument_errors(L):
     assert imp(R=7) == b.EARS_ERR_SHAPE
     assert imp(ts=P + 4) == b.EARS_ERR_ALIGN
     assert imp(wsb=8) == b.EARS_ERR_WORKSPACE
+
+
+def test_row_stats_argument_errors(L):
+    from paper_2512_13194_amd import binding as b
+
+    def rs(dtype=1, logits=P, rows=4, V=64, T=1.0, rowT=None, rmax=P, rsum=P):
+        return L.ears_row_stats(dtype, logits, rows, V, T, rowT, rmax, rsum, None)
+    assert rs(dtype=7) == b.EARS_ERR_DTYPE
+    assert rs(logits=None) == b.EARS_ERR_NULL and rs(rmax=None) == b.EARS_ERR_NULL
+    assert rs(rows=0) == b.EARS_ERR_SHAPE and rs(V=0) == b.EARS_ERR_SHAPE
+    assert rs(T=-1.0) == b.EARS_ERR_PARAM
+    assert rs(logits=P + 4) == b.EARS_ERR_ALIGN and rs(rsum=P + 4) == b.EARS_ERR_ALIGN

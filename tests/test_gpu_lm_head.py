@@ -138,3 +138,38 @@ def test_headline_shape_sampled(ears, oracle):
     for i, n in enumerate(rows):
         _, m, Z, _ = oracle.softmax(lb[i], T)
         assert rm[n] == m and abs(rs[n] - Z) <= 1e-5 * Z
+
+
+@pytest.mark.parametrize("dtype,V", [(torch.bfloat16, 32000), (torch.float32, 4099), (torch.bfloat16, 13)])
+def test_precomputed_row_statistics_feed_the_verification(ears, oracle, dtype, V):
+    """ears_row_stats on the draft and the target logits separately (as a pipeline would run it
+    after each model), imported, then DECIDE | SAMPLE: identical to the one-call path."""
+    from paper_2512_13194_amd import inputs
+    _log("row_stats -> import -> verify %s V=%d" % (dtype, V))
+    B, K, T, beta, seed = 10, 4, 0.7, 0.4, 5
+    batch = inputs.make_rect(B, K, V, dtype, T=T, data_seed=95, draft_noise=1.0, device="cuda")
+    dm, dz = ears.ears_row_stats(batch.draft, temperature=T)
+    tm, tz = ears.ears_row_stats(batch.target, temperature=T)
+    torch.cuda.synchronize()
+    tb = inputs.logits_to_numpy(batch.target).reshape(B * (K + 1), V)
+    for n in (0, 7, B * (K + 1) - 1):
+        _, m, Z, _ = oracle.softmax(tb[n], float(np.float32(T)))
+        assert tm.view(-1)[n].item() == m and abs(tz.view(-1)[n].item() - Z) <= 1e-5 * Z
+    ws = torch.empty(ears.ears_workspace_bytes(B * K, B, V), dtype=torch.uint8, device="cuda")
+    ears.ears_import_stats(batch.target, batch.draft, batch.tokens, tm.view(-1), tz.view(-1),
+                           dm.view(-1), dz.view(-1), ws)
+    out = ears.ears_verify_ex(batch.target, batch.draft, batch.tokens, temperature=T, beta=beta, seed=seed,
+                              workspace=ws, stages=ears.EARS_STAGE_DECIDE | ears.EARS_STAGE_SAMPLE,
+                              want_stats=True, want_path=True)
+    full = ears.ears_verify_ex(batch.target, batch.draft, batch.tokens, temperature=T, beta=beta, seed=seed,
+                               want_stats=True, want_path=True)
+    torch.cuda.synchronize()
+    assert torch.equal(out["accept_len"], full["accept_len"]) and torch.equal(out["tokens"], full["tokens"])
+    assert torch.equal(out["stats"], full["stats"]) and torch.equal(out["path"], full["path"])
+    ora = oracle.verify(inputs.logits_to_numpy(batch.target), inputs.logits_to_numpy(batch.draft),
+                        batch.tokens.cpu().numpy(), float(np.float32(T)), float(np.float32(beta)), seed,
+                        nthreads=NTHREADS)
+    rep = compare(ora, out["accept_len"].cpu().numpy(), out["tokens"].cpu().numpy(),
+                  out["stats"].cpu().numpy(), out["path"].cpu().numpy(), None, K,
+                  1e-5 if dtype == torch.float32 else 2e-3, batch.tokens.cpu().numpy(), V)
+    assert rep.exempt_decisions == 0 and rep.exempt_tokens == 0
