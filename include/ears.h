@@ -208,6 +208,8 @@ int ears_verify_greedy(int dtype, const void* target_logits, const int32_t* draf
  *   temperature      scalar T > 0, used when row_temperature is NULL
  *   row_temperature  device [N] float or NULL
  *   out_logits       [N, V] bf16;  out_row_max [N] float;  out_row_sumexp [N] double
+ *   out_row_entropy  [N] double or NULL: Shannon entropy (nats) of softmax(logits[n,:] / T), for
+ *                    the entropy-based uncertainty measure
  *   workspace        device, 256-byte aligned, >= ears_lm_head_workspace_bytes(N, V) bytes
  * N * V must be below 2^31.
  * ------------------------------------------------------------------------------------------- */
@@ -215,32 +217,35 @@ size_t ears_lm_head_workspace_bytes(int N, int V);
 
 int ears_lm_head_bf16(const void* hidden, const void* weight, int N, int D, int V,
                       float temperature, const float* row_temperature, void* out_logits,
-                      float* out_row_max, double* out_row_sumexp, void* workspace,
-                      size_t workspace_bytes, void* stream);
+                      float* out_row_max, double* out_row_sumexp, double* out_row_entropy,
+                      void* workspace, size_t workspace_bytes, void* stream);
 
 /* The same per-row statistics for logits that already exist: one streaming pass over the rows of
  * ONE matrix, [rows, V] row-major (16-byte aligned base), at temperature T (scalar, or per row when
  * row_temperature is not NULL).  A pipeline can run it on the draft logits as soon as the draft
  * model has produced them, and on the target logits after the target pass ("pre-computation",
  * Section 3.3 item 1), and hand both to ears_import_stats().
- *   out_row_max [rows] float, out_row_sumexp [rows] double */
+ *   out_row_max [rows] float, out_row_sumexp [rows] double, out_row_entropy [rows] double or NULL
+ *   (Shannon entropy in nats, for the entropy-based uncertainty measure) */
 int ears_row_stats(int dtype, const void* logits, int64_t rows, int V, float temperature,
                    const float* row_temperature, float* out_row_max, double* out_row_sumexp,
-                   void* stream);
+                   double* out_row_entropy, void* stream);
 
 /* Fills the statistics part of a verification workspace from per-row statistics computed by the
  * producers of the logits (ears_lm_head_bf16 for the target and for the draft model), and gathers
  * the draft tokens' logits.  Afterwards ears_verify_ex with stages DECIDE | SAMPLE (same batch,
- * same temperature(s), EARS_UNCERTAINTY_MAXPROB) completes the step without the statistics pass.
+ * same temperature(s)) completes the step without the statistics pass.
  *   target_row_max / target_row_sumexp   [total_draft_rows + B], packed like the target rows
+ *   target_row_entropy                   same shape, or NULL; required before a DECIDE stage
+ *                                        with EARS_UNCERTAINTY_ENTROPY
  *   draft_row_max / draft_row_sumexp     [total_draft_rows]
  * Other arguments as for ears_verify_ex. */
 int ears_import_stats(int dtype, const void* target_logits, const void* draft_logits,
                       const int32_t* draft_tokens, const int64_t* row_offsets,
                       int64_t total_draft_rows, int B, int K, int V, const float* target_row_max,
-                      const double* target_row_sumexp, const float* draft_row_max,
-                      const double* draft_row_sumexp, void* workspace, size_t workspace_bytes,
-                      void* stream);
+                      const double* target_row_sumexp, const double* target_row_entropy,
+                      const float* draft_row_max, const double* draft_row_sumexp, void* workspace,
+                      size_t workspace_bytes, void* stream);
 
 /* Frees the library-owned scratch of the simple entry points on every device (synchronises). */
 void ears_release(void);

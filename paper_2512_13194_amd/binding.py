@@ -65,12 +65,12 @@ def lib() -> ctypes.CDLL:
         L.ears_verify_greedy.restype = i32
         L.ears_lm_head_workspace_bytes.argtypes = [i32, i32]
         L.ears_lm_head_workspace_bytes.restype = sz
-        L.ears_lm_head_bf16.argtypes = [vp, vp, i32, i32, i32, f32, vp, vp, vp, vp, vp, sz, vp]
+        L.ears_lm_head_bf16.argtypes = [vp, vp, i32, i32, i32, f32, vp, vp, vp, vp, vp, vp, sz, vp]
         L.ears_lm_head_bf16.restype = i32
-        L.ears_row_stats.argtypes = [i32, vp, i64, i32, f32, vp, vp, vp, vp]
+        L.ears_row_stats.argtypes = [i32, vp, i64, i32, f32, vp, vp, vp, vp, vp]
         L.ears_row_stats.restype = i32
         L.ears_import_stats.argtypes = [i32, vp, vp, vp, vp, i64, i32, i32, i32, vp, vp, vp, vp, vp,
-                                        sz, vp]
+                                        vp, sz, vp]
         L.ears_import_stats.restype = i32
         L.ears_release.argtypes = []
         L.ears_release.restype = None
@@ -274,8 +274,10 @@ def ears_lm_head_workspace_bytes(N: int, V: int) -> int:
 
 
 def ears_lm_head_bf16(hidden, weight, *, temperature=1.0, row_temperature=None, out_logits=None,
-                      out_row_max=None, out_row_sumexp=None, workspace=None, stream=None):
-    """hidden [N,D] bf16, weight [V,D] bf16 -> (logits [N,V] bf16, row_max [N] f32, row_sumexp [N] f64)."""
+                      out_row_max=None, out_row_sumexp=None, out_row_entropy=None, workspace=None,
+                      stream=None):
+    """hidden [N,D] bf16, weight [V,D] bf16 -> (logits [N,V] bf16, row_max [N] f32, row_sumexp [N] f64);
+    out_row_entropy (f64 [N]) is filled when given."""
     _need(hidden, torch.bfloat16, "hidden")
     _need(weight, torch.bfloat16, "weight")
     N, D = hidden.shape
@@ -297,15 +299,18 @@ def ears_lm_head_bf16(hidden, weight, *, temperature=1.0, row_temperature=None, 
     if row_temperature is not None:
         _need(row_temperature, torch.float32, "row_temperature")
         assert row_temperature.numel() == N
+    if out_row_entropy is not None:
+        _need(out_row_entropy, torch.float64, "out_row_entropy")
+        assert out_row_entropy.numel() == N
     _check(lib().ears_lm_head_bf16(_ptr(hidden), _ptr(weight), N, D, V, float(temperature),
                                    _ptr(row_temperature), _ptr(out_logits), _ptr(out_row_max),
-                                   _ptr(out_row_sumexp), _ptr(workspace), workspace.numel(),
-                                   _stream(stream)))
+                                   _ptr(out_row_sumexp), _ptr(out_row_entropy), _ptr(workspace),
+                                   workspace.numel(), _stream(stream)))
     return out_logits, out_row_max, out_row_sumexp
 
 
 def ears_row_stats(logits, *, temperature=1.0, row_temperature=None, out_row_max=None,
-                   out_row_sumexp=None, stream=None):
+                   out_row_sumexp=None, out_row_entropy=None, stream=None):
     """Per-row (max, sum-exp) of logits [..., V] (f32 or bf16): returns (row_max f32, row_sumexp f64)
     shaped like the leading dimensions."""
     _need(logits, logits.dtype, "logits")
@@ -322,14 +327,18 @@ def ears_row_stats(logits, *, temperature=1.0, row_temperature=None, out_row_max
     if row_temperature is not None:
         _need(row_temperature, torch.float32, "row_temperature")
         assert row_temperature.numel() == rows
+    if out_row_entropy is not None:
+        _need(out_row_entropy, torch.float64, "out_row_entropy")
+        assert out_row_entropy.numel() == rows
     _check(lib().ears_row_stats(_dtype_code(logits), _ptr(logits), rows, V, float(temperature),
                                 _ptr(row_temperature), _ptr(out_row_max), _ptr(out_row_sumexp),
-                                _stream(stream)))
+                                _ptr(out_row_entropy), _stream(stream)))
     return out_row_max, out_row_sumexp
 
 
 def ears_import_stats(target_logits, draft_logits, draft_tokens, target_row_max, target_row_sumexp,
-                      draft_row_max, draft_row_sumexp, workspace, *, row_offsets=None, stream=None):
+                      draft_row_max, draft_row_sumexp, workspace, *, target_row_entropy=None,
+                      row_offsets=None, stream=None):
     """Fills `workspace` (uint8 CUDA tensor of ears_workspace_bytes) with producer-side statistics."""
     V = target_logits.shape[-1]
     if row_offsets is None:
@@ -346,11 +355,14 @@ def ears_import_stats(target_logits, draft_logits, draft_tokens, target_row_max,
     _need(draft_row_sumexp, torch.float64, "draft_row_sumexp")
     assert target_row_max.numel() == R + B == target_row_sumexp.numel()
     assert draft_row_max.numel() == R == draft_row_sumexp.numel()
+    if target_row_entropy is not None:
+        _need(target_row_entropy, torch.float64, "target_row_entropy")
+        assert target_row_entropy.numel() == R + B
     _check(lib().ears_import_stats(
         _dtype_code(target_logits), _ptr(target_logits), _ptr(draft_logits), _ptr(draft_tokens),
         _ptr(row_offsets), R, B, K, V, _ptr(target_row_max), _ptr(target_row_sumexp),
-        _ptr(draft_row_max), _ptr(draft_row_sumexp), _ptr(workspace), workspace.numel(),
-        _stream(stream)))
+        _ptr(target_row_entropy), _ptr(draft_row_max), _ptr(draft_row_sumexp), _ptr(workspace),
+        workspace.numel(), _stream(stream)))
     return workspace
 
 

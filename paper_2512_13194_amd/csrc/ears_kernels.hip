@@ -369,13 +369,13 @@ int ears_verify_greedy(int dtype, const void* target_logits, const int32_t* draf
 size_t ears_lm_head_workspace_bytes(int N, int V) {
   if (N < 1 || V < 1) return 0;
   const size_t nparts = (size_t)kLmPartsPerTile * (size_t)((V + kLmTile - 1) / kLmTile);
-  return 2 * align_up((size_t)N * nparts * sizeof(float), 256);
+  return 3 * align_up((size_t)N * nparts * sizeof(float), 256);
 }
 
 int ears_lm_head_bf16(const void* hidden, const void* weight, int N, int D, int V,
                       float temperature, const float* row_temperature, void* out_logits,
-                      float* out_row_max, double* out_row_sumexp, void* workspace,
-                      size_t workspace_bytes, void* stream) {
+                      float* out_row_max, double* out_row_sumexp, double* out_row_entropy,
+                      void* workspace, size_t workspace_bytes, void* stream) {
   if (!hidden || !weight || !out_logits || !out_row_max || !out_row_sumexp) return EARS_ERR_NULL;
   if (N < 1 || V < 1 || D < kLmBK || D % kLmBK != 0) return EARS_ERR_SHAPE;
   if ((int64_t)N * (int64_t)V > (int64_t)0x7FFFFFFF) return EARS_ERR_SHAPE;
@@ -384,7 +384,8 @@ int ears_lm_head_bf16(const void* hidden, const void* weight, int N, int D, int 
     return EARS_ERR_SHAPE;
   if (!row_temperature && !(std::isfinite(temperature) && temperature > 0.0f)) return EARS_ERR_PARAM;
   if (!aligned(hidden, 16) || !aligned(weight, 16) || !aligned(out_logits, 2) ||
-      !aligned(out_row_max, 4) || !aligned(out_row_sumexp, 8) || !aligned(row_temperature, 4))
+      !aligned(out_row_max, 4) || !aligned(out_row_sumexp, 8) || !aligned(out_row_entropy, 8) ||
+      !aligned(row_temperature, 4))
     return EARS_ERR_ALIGN;
   const size_t need = ears_lm_head_workspace_bytes(N, V);
   if (!workspace || workspace_bytes < need) return EARS_ERR_WORKSPACE;
@@ -402,9 +403,11 @@ int ears_lm_head_bf16(const void* hidden, const void* weight, int N, int D, int 
   p.logits = static_cast<uint16_t*>(out_logits);
   p.nparts = kLmPartsPerTile * p.n_vtiles;
   p.part_m = static_cast<float*>(workspace);
-  p.part_S = reinterpret_cast<float*>(static_cast<unsigned char*>(workspace) + need / 2);
+  p.part_S = reinterpret_cast<float*>(static_cast<unsigned char*>(workspace) + need / 3);
+  p.part_W = reinterpret_cast<float*>(static_cast<unsigned char*>(workspace) + 2 * (need / 3));
   p.row_m = out_row_max;
   p.row_Z = out_row_sumexp;
+  p.row_H = out_row_entropy;
   const int64_t groups = (int64_t)8 * ((p.n_vtiles + 7) / 8) * p.n_ttiles;
   if (groups > (int64_t)0x7FFFFFFF) return EARS_ERR_SHAPE;
   hipStream_t s = static_cast<hipStream_t>(stream);
@@ -416,13 +419,13 @@ int ears_lm_head_bf16(const void* hidden, const void* weight, int N, int D, int 
 
 int ears_row_stats(int dtype, const void* logits, int64_t rows, int V, float temperature,
                    const float* row_temperature, float* out_row_max, double* out_row_sumexp,
-                   void* stream) {
+                   double* out_row_entropy, void* stream) {
   if (dtype != EARS_F32 && dtype != EARS_BF16) return EARS_ERR_DTYPE;
   if (!logits || !out_row_max || !out_row_sumexp) return EARS_ERR_NULL;
   if (rows < 1 || rows > (int64_t)0x7FFFFFFF || V < 1) return EARS_ERR_SHAPE;
   if (!row_temperature && !(std::isfinite(temperature) && temperature > 0.0f)) return EARS_ERR_PARAM;
   if (!aligned(logits, 16) || !aligned(out_row_max, 4) || !aligned(out_row_sumexp, 8) ||
-      !aligned(row_temperature, 4))
+      !aligned(out_row_entropy, 8) || !aligned(row_temperature, 4))
     return EARS_ERR_ALIGN;
   RowStatsProblem p;
   p.logits = logits;
@@ -432,20 +435,26 @@ int ears_row_stats(int dtype, const void* logits, int64_t rows, int V, float tem
   p.row_T = row_temperature;
   p.row_m = out_row_max;
   p.row_Z = out_row_sumexp;
+  p.row_H = out_row_entropy;
   hipStream_t s = static_cast<hipStream_t>(stream);
-  if (dtype == EARS_F32)
-    hipLaunchKernelGGL((single_row_stats_kernel<F32, 4>), dim3((unsigned)rows), dim3(kBlock), 0, s, p);
+  const dim3 grid((unsigned)rows), block(kBlock);
+  if (dtype == EARS_F32 && out_row_entropy)
+    hipLaunchKernelGGL((single_row_stats_kernel<F32, 4, true>), grid, block, 0, s, p);
+  else if (dtype == EARS_F32)
+    hipLaunchKernelGGL((single_row_stats_kernel<F32, 4, false>), grid, block, 0, s, p);
+  else if (out_row_entropy)
+    hipLaunchKernelGGL((single_row_stats_kernel<BF16, 4, true>), grid, block, 0, s, p);
   else
-    hipLaunchKernelGGL((single_row_stats_kernel<BF16, 4>), dim3((unsigned)rows), dim3(kBlock), 0, s, p);
+    hipLaunchKernelGGL((single_row_stats_kernel<BF16, 4, false>), grid, block, 0, s, p);
   return hipGetLastError() == hipSuccess ? EARS_OK : EARS_ERR_HIP;
 }
 
 int ears_import_stats(int dtype, const void* target_logits, const void* draft_logits,
                       const int32_t* draft_tokens, const int64_t* row_offsets,
                       int64_t total_draft_rows, int B, int K, int V, const float* target_row_max,
-                      const double* target_row_sumexp, const float* draft_row_max,
-                      const double* draft_row_sumexp, void* workspace, size_t workspace_bytes,
-                      void* stream) {
+                      const double* target_row_sumexp, const double* target_row_entropy,
+                      const float* draft_row_max, const double* draft_row_sumexp, void* workspace,
+                      size_t workspace_bytes, void* stream) {
   if (!target_row_max || !target_row_sumexp || !draft_row_max || !draft_row_sumexp)
     return EARS_ERR_NULL;
   WorkspaceLayout lay;
@@ -457,7 +466,7 @@ int ears_import_stats(int dtype, const void* target_logits, const void* draft_lo
                           nullptr, &lay);
   if (rc != EARS_OK) return rc;
   if (!aligned(target_row_max, 4) || !aligned(draft_row_max, 4) || !aligned(target_row_sumexp, 8) ||
-      !aligned(draft_row_sumexp, 8))
+      !aligned(draft_row_sumexp, 8) || !aligned(target_row_entropy, 8))
     return EARS_ERR_ALIGN;
   Problem p = {};
   p.target = target_logits;
@@ -472,14 +481,15 @@ int ears_import_stats(int dtype, const void* target_logits, const void* draft_lo
   p.Z = reinterpret_cast<double*>(ws + lay.off_Z);
   p.m = reinterpret_cast<float*>(ws + lay.off_m);
   p.lx = reinterpret_cast<float*>(ws + lay.off_lx);
+  p.unc = reinterpret_cast<double*>(ws + lay.off_unc);
   hipStream_t s = static_cast<hipStream_t>(stream);
   const dim3 grid((unsigned)((total_draft_rows + kBlock - 1) / kBlock));
   if (dtype == EARS_F32)
     hipLaunchKernelGGL(import_stats_kernel<F32>, grid, dim3(kBlock), 0, s, p, target_row_max,
-                       target_row_sumexp, draft_row_max, draft_row_sumexp);
+                       target_row_sumexp, target_row_entropy, draft_row_max, draft_row_sumexp);
   else
     hipLaunchKernelGGL(import_stats_kernel<BF16>, grid, dim3(kBlock), 0, s, p, target_row_max,
-                       target_row_sumexp, draft_row_max, draft_row_sumexp);
+                       target_row_sumexp, target_row_entropy, draft_row_max, draft_row_sumexp);
   return hipGetLastError() == hipSuccess ? EARS_OK : EARS_ERR_HIP;
 }
 

@@ -38,10 +38,12 @@ struct LmHeadProblem {
   int n_vtiles, n_ttiles;   // tiles along the vocabulary and along the tokens
   uint16_t* logits;         // [N, V] bf16
   float* part_m;            // [N, nparts] maximum of the rounded logits of one 128-entry slice
-  float* part_S;            // [N, nparts] sum of exp2(l*c - fl(m*c)) over the slice
+  float* part_S;            // [N, nparts] sum of e = exp2(y), y = l*c - fl(m*c), over the slice
+  float* part_W;            // [N, nparts] sum of e*y over the slice (for the entropy)
   int nparts;               // 2 * n_vtiles
   float* row_m;             // [N]
   double* row_Z;            // [N]
+  double* row_H;            // [N] Shannon entropy (nats) of softmax(row / T), or nullptr
 };
 
 typedef __bf16 lm_bf16x8 __attribute__((ext_vector_type(8)));
@@ -227,21 +229,30 @@ void lm_head_kernel(LmHeadProblem p) {
     }
     // the other half-wave holds the other 64 entries of the same token's 128-slice
     m = fmaxf(m, __shfl_xor(m, 32, 64));
-    float S = 0.0f;
+    float S = 0.0f, W = 0.0f;
     if (m != -INFINITY) {
       const float mc = m * c;
       float s4[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+      float w4[4] = {0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
       for (int i = 0; i < 4; ++i)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) s4[r & 3] += __builtin_amdgcn_exp2f(fmaf(xr[i][r], c, -mc));
+        for (int r = 0; r < 16; ++r) {
+          const float y = fmaxf(fmaf(xr[i][r], c, -mc), -126.0f);  // a masked entry adds 0 * finite
+          const float e = __builtin_amdgcn_exp2f(y);
+          s4[r & 3] += e;
+          w4[r & 3] = fmaf(e, y, w4[r & 3]);
+        }
       S = (s4[0] + s4[1]) + (s4[2] + s4[3]);
+      W = (w4[0] + w4[1]) + (w4[2] + w4[3]);
     }
     S += __shfl_xor(S, 32, 64);
+    W += __shfl_xor(W, 32, 64);
     if (half == 0 && tok < p.N) {
       const size_t slot = (size_t)tok * p.nparts + vt * kLmPartsPerTile + wv;
       p.part_m[slot] = m;
       p.part_S[slot] = S;
+      p.part_W[slot] = W;
     }
   }
   __syncthreads();
@@ -267,7 +278,9 @@ void lm_head_kernel(LmHeadProblem p) {
 }
 
 // Merges the per-slice partials of one token row with the associative rule of the statistics pass:
-// M = max m, Z = sum S * 2^(fl(m c) - fl(M c)) in fp64, then the rounding of fl(M c) undone.
+// M = max m, Z = sum S * 2^d, W = sum 2^d (W_p + d S_p) with d = fl(m c) - fl(M c), in fp64; then
+// the rounding of fl(M c) is undone for Z, and H = ln Z - ln 2 * W / Z (the offset's rounding shifts
+// both terms of H equally).
 __global__ __launch_bounds__(kBlock) void lm_head_merge_kernel(LmHeadProblem p) {
   const int lane = (int)threadIdx.x & (kWave - 1);
   const int row = (int)blockIdx.x * kWavesPerBlock + (int)threadIdx.x / kWave;
@@ -276,19 +289,27 @@ __global__ __launch_bounds__(kBlock) void lm_head_merge_kernel(LmHeadProblem p) 
   const float c = (float)(kLog2e / (double)T);
   const float* pm = p.part_m + (size_t)row * p.nparts;
   const float* pS = p.part_S + (size_t)row * p.nparts;
+  const float* pW = p.part_W + (size_t)row * p.nparts;
   float M = -INFINITY;
   for (int i = lane; i < p.nparts; i += kWave) M = fmaxf(M, pm[i]);
   M = wave_max(M);
   const float Mc = M * c;
-  double Z = 0.0;
+  double Z = 0.0, W = 0.0;
   for (int i = lane; i < p.nparts; i += kWave) {
     const float m = pm[i];
-    if (m != -INFINITY) Z += (double)pS[i] * exp2((double)(m * c) - (double)Mc);
+    if (m != -INFINITY) {
+      const double d = (double)(m * c) - (double)Mc;
+      const double scale = exp2(d);
+      Z += (double)pS[i] * scale;
+      W += scale * ((double)pW[i] + d * (double)pS[i]);
+    }
   }
   Z = wave_sum(Z);
+  W = wave_sum(W);
   if (lane == 0) {
     p.row_m[row] = M;
     p.row_Z[row] = Z * exp2((double)Mc - (double)M * (double)c);
+    if (p.row_H) p.row_H[row] = log(Z) - 0.69314718055994530942 * (W / Z);
   }
 }
 
@@ -297,6 +318,7 @@ __global__ __launch_bounds__(kBlock) void lm_head_merge_kernel(LmHeadProblem p) 
 template <typename DT>
 __global__ __launch_bounds__(kBlock) void import_stats_kernel(Problem p, const float* t_max,
                                                                const double* t_sum,
+                                                               const double* t_entropy,
                                                                const float* d_max,
                                                                const double* d_sum) {
   const int64_t r = (int64_t)blockIdx.x * kBlock + threadIdx.x;
@@ -314,6 +336,9 @@ __global__ __launch_bounds__(kBlock) void import_stats_kernel(Problem p, const f
   p.m[2 * r + 1] = d_max[r];
   p.lx[2 * r] = lxt;
   p.lx[2 * r + 1] = lxd;
+  // entropy-based uncertainty H / log V of the target row (Section 5), when the producer has it
+  if (t_entropy)
+    p.unc[r] = p.V > 1 ? fmin(fmax(t_entropy[r + b] / log((double)p.V), 0.0), 1.0) : 0.0;
 }
 
 }  // namespace ears

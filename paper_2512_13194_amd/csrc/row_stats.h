@@ -201,9 +201,10 @@ struct RowStatsProblem {
   const float* row_T;  // [rows] or nullptr
   float* row_m;        // [rows]
   double* row_Z;       // [rows]
+  double* row_H;       // [rows] Shannon entropy in nats (only with kEntropy)
 };
 
-template <typename DT, int kUnroll>
+template <typename DT, int kUnroll, bool kEntropy>
 __global__ __launch_bounds__(kBlock) void single_row_stats_kernel(RowStatsProblem p) {
   using storage = typename DT::storage;
   __shared__ float sh_m[kWavesPerBlock];
@@ -213,11 +214,12 @@ __global__ __launch_bounds__(kBlock) void single_row_stats_kernel(RowStatsProble
   const float c = (float)(kLog2e / (double)T);
   float M = 0.0f;
   double Z = 0.0, H = 0.0;
-  row_pass<DT, kUnroll, false>(static_cast<const storage*>(p.logits) + row * (int64_t)p.V, p.V, c,
-                               sh_m, sh_s, M, Z, H);
+  row_pass<DT, kUnroll, kEntropy>(static_cast<const storage*>(p.logits) + row * (int64_t)p.V, p.V,
+                                  c, sh_m, sh_s, M, Z, H);
   if (threadIdx.x == 0) {
     p.row_m[row] = M;
     p.row_Z[row] = Z;
+    if (kEntropy) p.row_H[row] = H;
   }
 }
 

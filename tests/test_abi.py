@@ -169,13 +169,13 @@ def test_greedy_argument_errors(L):
 
 def _lm(L, hidden=P, weight=P, N=8, D=128, V=100, T=1.0, rowT=None, logits=P, rmax=P, rsum=P,
         ws=P, wsb=1 << 20):
-    return L.ears_lm_head_bf16(hidden, weight, N, D, V, T, rowT, logits, rmax, rsum, ws, wsb, None)
+    return L.ears_lm_head_bf16(hidden, weight, N, D, V, T, rowT, logits, rmax, rsum, None, ws, wsb, None)
 
 
 def test_lm_head_argument_errors(L):
     from paper_2512_13194_amd import binding as b
     w = b.ears_lm_head_workspace_bytes(2304, 128256)
-    assert w >= 2 * 2304 * 2 * 501 * 4 and w % 256 == 0
+    assert w >= 3 * 2304 * 2 * 501 * 4 and w % 256 == 0
     assert b.ears_lm_head_workspace_bytes(0, 5) == 0 and b.ears_lm_head_workspace_bytes(5, 0) == 0
     for name in ("hidden", "weight", "logits", "rmax", "rsum"):
         assert _lm(L, **{name: None}) == b.EARS_ERR_NULL
@@ -199,8 +199,8 @@ def test_import_stats_argument_errors(L):
 
     def imp(dtype=1, target=P, draft=P, tokens=P, off=None, R=6, B=2, K=3, V=64, tm=P, ts=P, dm=P,
             ds=P, ws=P, wsb=1 << 20):
-        return L.ears_import_stats(dtype, target, draft, tokens, off, R, B, K, V, tm, ts, dm, ds, ws,
-                                   wsb, None)
+        return L.ears_import_stats(dtype, target, draft, tokens, off, R, B, K, V, tm, ts, None, dm, ds,
+                                   ws, wsb, None)
     for name in ("tm", "ts", "dm", "ds", "target", "draft", "tokens"):
         assert imp(**{name: None}) == b.EARS_ERR_NULL
     assert imp(dtype=3) == b.EARS_ERR_DTYPE
@@ -213,7 +213,7 @@ def test_row_stats_argument_errors(L):
     from paper_2512_13194_amd import binding as b
 
     def rs(dtype=1, logits=P, rows=4, V=64, T=1.0, rowT=None, rmax=P, rsum=P):
-        return L.ears_row_stats(dtype, logits, rows, V, T, rowT, rmax, rsum, None)
+        return L.ears_row_stats(dtype, logits, rows, V, T, rowT, rmax, rsum, None, None)
     assert rs(dtype=7) == b.EARS_ERR_DTYPE
     assert rs(logits=None) == b.EARS_ERR_NULL and rs(rmax=None) == b.EARS_ERR_NULL
     assert rs(rows=0) == b.EARS_ERR_SHAPE and rs(V=0) == b.EARS_ERR_SHAPE

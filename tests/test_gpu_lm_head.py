@@ -173,3 +173,43 @@ def test_precomputed_row_statistics_feed_the_verification(ears, oracle, dtype, V
                   out["stats"].cpu().numpy(), out["path"].cpu().numpy(), None, K,
                   1e-5 if dtype == torch.float32 else 2e-3, batch.tokens.cpu().numpy(), V)
     assert rep.exempt_decisions == 0 and rep.exempt_tokens == 0
+
+
+def test_entropy_measure_from_producer_side_statistics(ears, oracle):
+    """Entropy of the emitted rows from the projection's epilogue and from ears_row_stats, against
+    the oracle; imported, the DECIDE stage with the entropy measure gives the oracle's decisions."""
+    _log("entropy through lm_head / row_stats / import")
+    B, K, V, D, T, beta, seed = 10, 3, 3000, 128, 0.8, 0.6, 23
+    ht, wt = _operands(B * (K + 1), D, V, seed=31)
+    g = torch.Generator(device="cuda").manual_seed(32)
+    wd = (wt.float() + 0.08 * torch.randn(V, D, generator=g, device="cuda")).to(torch.bfloat16)
+    hd = ht.view(B, K + 1, D)[:, :K].reshape(B * K, D).contiguous()
+    th = torch.empty(B * (K + 1), dtype=torch.float64, device="cuda")
+    tl, tm, tz = ears.ears_lm_head_bf16(ht, wt, temperature=T, out_row_entropy=th)
+    dl, dm, dz = ears.ears_lm_head_bf16(hd, wd, temperature=T)
+    th2 = torch.empty_like(th)
+    tm2, tz2 = ears.ears_row_stats(tl, temperature=T, out_row_entropy=th2)
+    torch.cuda.synchronize()
+    bits = _bits(tl)
+    for n in range(B * (K + 1)):
+        p, m, Z, _ = oracle.softmax(bits[n], float(np.float32(T)))
+        H = oracle.entropy(p)
+        assert abs(th[n].item() - H) <= 2e-6 and abs(th2[n].item() - H) <= 2e-6, (n, th[n].item(), th2[n].item(), H)
+    assert torch.equal(tm, tm2)
+    target, draft = tl.view(B, K + 1, V), dl.view(B, K, V)
+    tokens = torch.multinomial(torch.softmax(draft.float().view(B * K, V) / T, -1), 1,
+                               generator=g).view(B, K).to(torch.int32)
+    ws = torch.empty(ears.ears_workspace_bytes(B * K, B, V), dtype=torch.uint8, device="cuda")
+    ears.ears_import_stats(target, draft, tokens, tm, tz, dm, dz, ws, target_row_entropy=th)
+    out = ears.ears_verify_ex(target, draft, tokens, temperature=T, beta=beta, seed=seed, workspace=ws,
+                              uncertainty=ears.EARS_UNCERTAINTY_ENTROPY,
+                              stages=ears.EARS_STAGE_DECIDE | ears.EARS_STAGE_SAMPLE,
+                              want_stats=True, want_path=True)
+    torch.cuda.synchronize()
+    ora = oracle.verify(_bits(target), _bits(draft), tokens.cpu().numpy(), float(np.float32(T)),
+                        float(np.float32(beta)), seed, nthreads=NTHREADS, uncertainty=oracle.UNC_ENTROPY)
+    rep = compare(ora, out["accept_len"].cpu().numpy(), out["tokens"].cpu().numpy(),
+                  out["stats"].cpu().numpy(), out["path"].cpu().numpy(), None, K, 2e-3,
+                  tokens.cpu().numpy(), V, unc_is_maxprob=False)
+    assert rep.exempt_decisions == 0 and rep.exempt_tokens == 0
+    assert (ora.path == 2).any()                  # the tolerance did decide some positions
