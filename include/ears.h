@@ -49,7 +49,7 @@ extern "C" {
 typedef enum ears_status {
   EARS_OK = 0,
   EARS_ERR_NULL = 1,      /* a required pointer is NULL */
-  EARS_ERR_SHAPE = 2,     /* B, K, V or total_draft_rows out of range (B at most 65535) */
+  EARS_ERR_SHAPE = 2,     /* B, K, V or total_draft_rows out of range */
   EARS_ERR_PARAM = 3,     /* temperature not finite or <= 0; beta not finite or < 0; bad stages
                              or uncertainty measure */
   EARS_ERR_ALIGN = 4,     /* a pointer is not aligned as documented */

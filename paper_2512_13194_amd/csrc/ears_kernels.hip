@@ -86,7 +86,6 @@ static int validate(int dtype, const void* target, const void* draft, const int3
   if (dtype != EARS_F32 && dtype != EARS_BF16) return EARS_ERR_DTYPE;
   if (!target || !draft || !tokens || !out_accept_len || !out_tokens) return EARS_ERR_NULL;
   if (B < 1 || V < 1 || R < 1) return EARS_ERR_SHAPE;
-  if (B > 65535) return EARS_ERR_SHAPE;  // the sampling stage puts the sequence on a grid's y axis
   if (row_offsets == nullptr) {
     if (K < 1 || (int64_t)B * (int64_t)K != R) return EARS_ERR_SHAPE;
   }
