@@ -298,10 +298,11 @@ __global__ __launch_bounds__(kBlock) void lm_head_merge_kernel(LmHeadProblem p) 
   for (int i = lane; i < p.nparts; i += kWave) {
     const float m = pm[i];
     if (m != -INFINITY) {
-      const double d = (double)(m * c) - (double)Mc;
-      const double scale = exp2(d);
+      // as in the lanes of the statistics pass: the rescaling factor in fp32, the sums in fp64
+      const float d = m * c - Mc;
+      const double scale = (double)__builtin_amdgcn_exp2f(d);
       Z += (double)pS[i] * scale;
-      W += scale * ((double)pW[i] + d * (double)pS[i]);
+      W += scale * ((double)pW[i] + (double)d * (double)pS[i]);
     }
   }
   Z = wave_sum(Z);
