@@ -63,24 +63,37 @@ __device__ __forceinline__ uint32_t philox_pick(const Philox blk, uint32_t v) {
   return (v & 2u) ? hi : lo;
 }
 
-// Level 3: the score exactly as defined, fp64.  -inf means "not a candidate".
+// The statistics pass sums exponentials in fp32 lanes: its Z is within this relative distance of
+// the fp64 sum (measured: 4.3e-7 at most).  p_t(v) - p_d(v) inherits an absolute uncertainty of
+// kZRelError * (p_t + p_d), which matters where the two nearly cancel.
+constexpr double kZRelError = 1.0e-6;
+
+// Level 3: the score exactly as defined, fp64.  -inf means "not a candidate".  With `lo` / `hi` the
+// score's range under the uncertainty of the cached Z is returned as well (residual mode; the
+// other modes have lo = hi = score).
 template <typename DT>
-__device__ double exact_score(const SampleCtx& c, int v, int mode) {
+__device__ double exact_score(const SampleCtx& c, int v, int mode, double* lo = nullptr,
+                              double* hi = nullptr) {
   const double lt = (double)DT::load(c.trow, v);
-  double logw;
+  double logw, logw_lo, logw_hi;
+  if (lo) *lo = -INFINITY;
+  if (hi) *hi = -INFINITY;
   if (mode == kModeBonus) {
     if (!(lt > -INFINITY)) return -INFINITY;
-    logw = lt / c.T;
+    logw = logw_lo = logw_hi = lt / c.T;
   } else {
     const double pt = exp((lt - c.mt) / c.T) / c.Zt;
     if (mode == kModeResidual) {
       const double pd = exp(((double)DT::load(c.drow, v) - c.md) / c.T) / c.Zd;
       const double q = pt - pd;
-      if (!(q > 0.0)) return -INFINITY;
-      logw = log(q);
+      const double dq = kZRelError * (pt + pd);
+      if (!(q + dq > 0.0)) return -INFINITY;
+      logw_hi = log(q + dq);
+      logw_lo = (q - dq > 0.0) ? log(q - dq) : -INFINITY;
+      logw = (q > 0.0) ? log(q) : -INFINITY;
     } else {
       if (!(pt > 0.0)) return -INFINITY;
-      logw = log(pt);
+      logw = logw_lo = logw_hi = log(pt);
     }
   }
   const uint32_t cw = philox_pick(noise_block(c.seed, c.seq, c.pos, kDomainCoarse, (uint32_t)v >> 4),
@@ -89,7 +102,30 @@ __device__ double exact_score(const SampleCtx& c, int v, int mode) {
   const uint32_t f = philox_pick(noise_block(c.seed, c.seq, c.pos, kDomainFine, (uint32_t)v >> 2),
                                  (uint32_t)v);
   const double u = ((double)h + ((double)f + 0.5) * 0x1p-32) * 0x1p-8;
-  return logw - log(-log(u));
+  const double g = -log(-log(u));
+  if (lo) *lo = logw_lo + g;
+  if (hi) *hi = logw_hi + g;
+  return logw + g;
+}
+
+// Z = sum_v exp((l_v - m) / T) of one row, fp64 throughout, by the whole workgroup (slow: only for
+// rows whose winner the cached Z cannot settle).
+template <typename DT>
+__device__ double block_sumexp64(const void* row, int V, double m, double T) {
+  __shared__ double sh_part[kWavesPerBlock];
+  double acc = 0.0;
+  for (int v = (int)threadIdx.x; v < V; v += kBlock) {
+    const double l = (double)DT::load(row, v);
+    if (l > -INFINITY) acc += exp((l - m) / T);
+  }
+  acc = wave_sum(acc);
+  __syncthreads();
+  if (((int)threadIdx.x & (kWave - 1)) == 0) sh_part[(int)threadIdx.x / kWave] = acc;
+  __syncthreads();
+  double Z = 0.0;
+#pragma unroll
+  for (int w = 0; w < kWavesPerBlock; ++w) Z += sh_part[w];
+  return Z;
 }
 
 __device__ Best block_best(Best x) {
@@ -482,28 +518,83 @@ __global__ __launch_bounds__(kBlock) void select_kernel(Problem p) {
   ctx.pos = (uint32_t)n;
   ctx.V = V;
   const int mode = residual ? kModeResidual : kModeBonus;
-  Best best{-INFINITY, -1};
-  if (separable) {
+  __shared__ double sh_lo_best;
+  // replaces the cached Z of both rows by fp64 sums: after it the scores are the definition's
+  auto make_exact = [&]() {
+    ctx.Zt = block_sumexp64<DT>(ctx.trow, V, ctx.mt, ctx.T);
+    ctx.Zd = block_sumexp64<DT>(ctx.drow, V, ctx.md, ctx.T);
+  };
+  // Scores of the surviving entries; a thread keeps what it computed for its first entry, so the
+  // second pass (ranges) costs nothing more in the usual case of at most one entry per thread.
+  int c_v = -1;
+  double c_s = -INFINITY, c_lo = -INFINITY, c_hi = -INFINITY;
+  auto score_survivors = [&](bool with_range, int skip_v, Best& out, double& lo_of_skip) {
+    // out: arg-max of the score (with_range false) or of the upper ends over v != skip_v (true)
     for (int idx = tid; idx < total; idx += kBlock) {
       const int i = idx / kRecordCap, j = idx - i * kRecordCap;
       const uint32_t* rc = recs + (size_t)i * kRecordWords;
       if (is_survivor((int)rc[1], j, __uint_as_float(rc[3 + 2 * j]))) {
         const int v = (int)rc[2 + 2 * j];
-        const double sc = exact_score<DT>(ctx, v, mode);
-        if (sc > -INFINITY && better(sc, v, best)) best = Best{sc, v};
+        double sc, lo, hi;
+        if (idx == tid && c_v == v) {
+          sc = c_s; lo = c_lo; hi = c_hi;
+        } else {
+          sc = exact_score<DT>(ctx, v, mode, &lo, &hi);
+          if (idx == tid) { c_v = v; c_s = sc; c_lo = lo; c_hi = hi; }
+        }
+        if (!with_range) {
+          if (sc > -INFINITY && better(sc, v, out)) out = Best{sc, v};
+        } else if (v == skip_v) {
+          lo_of_skip = lo;
+        } else if (hi > -INFINITY && better(hi, v, out)) {
+          out = Best{hi, v};
+        }
       }
     }
-    for (int i = 0; i < p.S; ++i) {
-      if ((int)recs[(size_t)i * kRecordWords + 1] == kRecordOverflow) {
-        const int c0 = i * p.chunk;
-        const int c1 = (V - c0) < p.chunk ? V : c0 + p.chunk;
-        best = exact_scan<DT>(ctx, c0, c1, mode, best);
-      }
-    }
+  };
+  Best best{-INFINITY, -1};
+  double unused = 0.0;
+  if (separable && !any_overflow) {
+    score_survivors(false, -1, best, unused);
     best = block_best(best);
+    if (residual) {
+      // Is the winner beyond the reach of the cached Z's uncertainty?  Its lowest possible score
+      // must exceed the highest possible score of every other survivor.
+      Best rival{-INFINITY, -1};
+      double lo_best = -INFINITY;
+      if (tid == 0) sh_lo_best = -INFINITY;
+      __syncthreads();
+      score_survivors(true, best.v, rival, lo_best);
+      if (lo_best > -INFINITY) sh_lo_best = lo_best;  // one thread owns the winner's entry
+      rival = block_best(rival);
+      __syncthreads();
+      const bool settled = best.v >= 0 && (rival.v < 0 || sh_lo_best > rival.s);
+      if (!settled) {
+        make_exact();
+        c_v = -1;  // cached scores used the cached Z
+        best = Best{-INFINITY, -1};
+        score_survivors(false, -1, best, unused);
+        best = block_best(best);
+      }
+    }
+  } else {
+    if (residual) make_exact();
+    if (separable) {
+      score_survivors(false, -1, best, unused);
+      for (int i = 0; i < p.S; ++i) {
+        if ((int)recs[(size_t)i * kRecordWords + 1] == kRecordOverflow) {
+          const int c0 = i * p.chunk;
+          const int c1 = (V - c0) < p.chunk ? V : c0 + p.chunk;
+          best = exact_scan<DT>(ctx, c0, c1, mode, best);
+        }
+      }
+      best = block_best(best);
+    }
   }
   if (best.v < 0) {
-    // the bounds could not separate this row: evaluate the definition over the whole row
+    // the bounds could not separate this row, or no survivor has a positive residual: evaluate the
+    // definition over the whole row (with fp64 sums for Z: make_exact is idempotent)
+    if (residual) make_exact();
     best = block_best(exact_scan<DT>(ctx, 0, V, mode, Best{-INFINITY, -1}));
     if (best.v < 0 && residual)  // empty residual: draw from the target distribution itself
       best = block_best(exact_scan<DT>(ctx, 0, V, kModeTargetFallback, Best{-INFINITY, -1}));

@@ -178,6 +178,38 @@ def test_empty_residual_fallback_and_bad_token(ears, oracle):
     assert rep.exempt_decisions == 0 and rep.exempt_tokens == 0
 
 
+def test_residual_where_target_and_draft_nearly_cancel(ears, oracle):
+    """Both rows put 1 - 5e-7 on the same entry and differ there by 3e-9: the residual's sign at that
+    entry is beyond the fp32-summed statistics, and its remaining mass (2e-8) sits elsewhere.  The
+    sampling stage has to notice and settle it with fp64 sums."""
+    _log("near-cancelling residual")
+    lt = torch.tensor([-13.7841835, -2.2866478, float("-inf"), 10.7803545, -4.74301386])
+    ld = torch.tensor([-14.6387682, -1.9834125, float("-inf"), 11.04857826, -5.57233429])
+    for dtype, V in ((torch.float32, 5), (torch.float32, 9000)):
+        B, K, T = 512, 1, 0.9
+        t = torch.full((V,), float("-inf"))
+        d = torch.full((V,), float("-inf"))
+        t[:5], d[:5] = lt, ld
+        if V > 5:                                   # a long tail far below, so that tiles and chunks exist
+            t[5:] = -60.0 - torch.rand(V - 5) * 5
+            d[5:] = -60.0 - torch.rand(V - 5) * 5
+        target = t.to(dtype).expand(B, K + 1, V).contiguous().cuda()
+        draft = d.to(dtype).expand(B, K, V).contiguous().cuda()
+        tokens = torch.full((B, K), 1, dtype=torch.int32, device="cuda")   # R = 0.96: a few rejections
+        out = ears.ears_verify_ex(target, draft, tokens, temperature=T, beta=0.0, seed=99,
+                                  want_stats=True, want_path=True)
+        torch.cuda.synchronize()
+        from paper_2512_13194_amd import inputs
+        ora = oracle.verify(inputs.logits_to_numpy(target), inputs.logits_to_numpy(draft),
+                            tokens.cpu().numpy(), float(np.float32(T)), 0.0, 99, nthreads=NTHREADS)
+        rejected = int((ora.accept_len == 0).sum())
+        assert 5 <= rejected <= 60
+        assert np.array_equal(out["accept_len"].cpu().numpy(), ora.accept_len)
+        assert np.array_equal(out["tokens"].view(B, K + 1).cpu().numpy(), ora.tokens)
+        # the replacement is never the entry where the two rows cancel
+        assert not (ora.tokens[ora.accept_len == 0, 0] == 3).any()
+
+
 def test_seq_ids_batch_order_invariance_and_determinism(ears, oracle):
     from paper_2512_13194_amd import inputs
     _log("seq ids / determinism")
