@@ -204,7 +204,11 @@ int ears_oracle_verify_seq(const void* target_rows, const void* draft_rows, cons
     mode = 0.0;
     int any = 0;
     for (int v = 0; v < V; ++v) {
+      /* p_t and p_d are fp64 softmax values, each good to a few units in the 16th digit; where
+       * they agree to 2^-40 relative their difference is rounding noise, not residual mass, and
+       * the entry is outside the residual's support */
       double q = pt[v] - pd[v];
+      if (q <= EARS_ORACLE_RESIDUAL_FLOOR * (pt[v] + pd[v])) q = 0.0;
       if (q > 0.0) {
         any = 1;
         top2_push(&top, log(q) + ears_oracle_gumbel(seed, seq_id, (uint32_t)n, (uint32_t)v), v);

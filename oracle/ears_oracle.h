@@ -53,6 +53,13 @@ extern "C" {
 
 /* uncertainty measure that scales the tolerance: the paper's 1 - max P_t (Section 3.2), or the
  * normalised Shannon entropy H(P_t) / log V (the "distribution entropy" of Section 5) */
+/* Support of the residual distribution norm(max(0, p_t - p_d)): an entry belongs to it when
+ * p_t(v) - p_d(v) exceeds this fraction of p_t(v) + p_d(v).  2^-40 is far above the rounding noise
+ * of an fp64 softmax (about 2^-50 relative) and far below anything a sampler can resolve (it
+ * removes at most 2^-39 of probability mass); without it, entries where the two rows agree exactly
+ * in real arithmetic enter or leave the support by the accident of a summation order. */
+#define EARS_ORACLE_RESIDUAL_FLOOR 0x1p-40
+
 #define EARS_ORACLE_UNC_MAXPROB 0
 #define EARS_ORACLE_UNC_ENTROPY 1
 

@@ -53,6 +53,7 @@ struct SampleCtx {
   uint64_t seed, seq;
   uint32_t pos;
   int V;
+  bool exact;  // Zt and Zd are fp64 sums (not the statistics pass's fp32-lane sums)
 };
 
 // word v & 3 of a block, by value selects (no indexed access to the block)
@@ -67,6 +68,9 @@ __device__ __forceinline__ uint32_t philox_pick(const Philox blk, uint32_t v) {
 // the fp64 sum (measured: 4.3e-7 at most).  p_t(v) - p_d(v) inherits an absolute uncertainty of
 // kZRelError * (p_t + p_d), which matters where the two nearly cancel.
 constexpr double kZRelError = 1.0e-6;
+// Support of the residual: p_t(v) - p_d(v) must exceed this fraction of p_t(v) + p_d(v); below it the
+// difference of two fp64 softmax values is rounding noise (same constant on the checking side).
+constexpr double kResidualFloor = 0x1p-40;
 
 // Level 3: the score exactly as defined, fp64.  -inf means "not a candidate".  With `lo` / `hi` the
 // score's range under the uncertainty of the cached Z is returned as well (residual mode; the
@@ -86,11 +90,13 @@ __device__ double exact_score(const SampleCtx& c, int v, int mode, double* lo = 
     if (mode == kModeResidual) {
       const double pd = exp(((double)DT::load(c.drow, v) - c.md) / c.T) / c.Zd;
       const double q = pt - pd;
-      const double dq = kZRelError * (pt + pd);
-      if (!(q + dq > 0.0)) return -INFINITY;
+      const double floor_q = kResidualFloor * (pt + pd);
+      // with the cached Z the difference is only known to within dq; with fp64 sums it is exact
+      const double dq = c.exact ? 0.0 : kZRelError * (pt + pd);
+      if (!(q + dq > floor_q)) return -INFINITY;
       logw_hi = log(q + dq);
-      logw_lo = (q - dq > 0.0) ? log(q - dq) : -INFINITY;
-      logw = (q > 0.0) ? log(q) : -INFINITY;
+      logw_lo = (q - dq > floor_q) ? log(q - dq) : -INFINITY;
+      logw = (q > floor_q) ? log(q) : -INFINITY;
     } else {
       if (!(pt > 0.0)) return -INFINITY;
       logw = logw_lo = logw_hi = log(pt);
@@ -517,12 +523,15 @@ __global__ __launch_bounds__(kBlock) void select_kernel(Problem p) {
   ctx.seq = seq_rng_id(p, b);
   ctx.pos = (uint32_t)n;
   ctx.V = V;
+  ctx.exact = false;
   const int mode = residual ? kModeResidual : kModeBonus;
   __shared__ double sh_lo_best;
   // replaces the cached Z of both rows by fp64 sums: after it the scores are the definition's
   auto make_exact = [&]() {
+    if (ctx.exact) return;  // uniform
     ctx.Zt = block_sumexp64<DT>(ctx.trow, V, ctx.mt, ctx.T);
     ctx.Zd = block_sumexp64<DT>(ctx.drow, V, ctx.md, ctx.T);
+    ctx.exact = true;
   };
   // Scores of the surviving entries; a thread keeps what it computed for its first entry, so the
   // second pass (ranges) costs nothing more in the usual case of at most one entry per thread.

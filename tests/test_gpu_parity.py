@@ -210,6 +210,23 @@ def test_residual_where_target_and_draft_nearly_cancel(ears, oracle):
         assert not (ora.tokens[ora.accept_len == 0, 0] == 3).any()
 
 
+def test_residual_support_floor_on_nearly_identical_peaked_rows(ears, oracle):
+    """Nearly identical, sharply peaked rows in bf16 with arbitrary draft tokens: almost every entry
+    has equal logits in both rows, so p_t - p_d there is the normalisers' rounding noise and must
+    stay out of the residual's support on both sides (the oracle's 2^-40 floor)."""
+    from paper_2512_13194_amd import inputs
+    _log("nearly identical peaked rows")
+    for V, sig, noise, seed in ((500, 6.0, 1e-3, 6393807171935209006), (4097, 12.0, 1e-2, 3), (33, 20.0, 0.0, 4)):
+        B, K, T = 200, 1, 0.5
+        batch = inputs.make_rect(B, K, V, torch.bfloat16, T=T, data_seed=1905728844, draft_noise=noise,
+                                 peaked_frac=1.0, peaked_sigma=sig, device="cuda")
+        g = torch.Generator(device="cuda").manual_seed(V)
+        batch.tokens = torch.randint(0, V, (B, K), device="cuda", dtype=torch.int32, generator=g)
+        rep, ora, _ = run_rect(ears, oracle, batch, T, 0.0, seed)
+        assert rep.exempt_decisions == 0 and rep.exempt_tokens == 0
+        assert (ora.accept_len == 0).sum() > B // 2
+
+
 def test_seq_ids_batch_order_invariance_and_determinism(ears, oracle):
     from paper_2512_13194_amd import inputs
     _log("seq ids / determinism")

@@ -34,8 +34,9 @@ MUTANTS = [
     ("strict_comparison", "} else if (R >= thr) {", "} else if (R > thr) {", PINS[1:2]),
     ("accept_length_off_by_one", "      n = i; /* x_i", "      n = i + 1; /* x_i", PINS[1:2]),
     ("later_rejection_wins", "if (decision == 0 && !first_reject_seen) {", "if (decision == 0) {", PINS[1:2]),
-    ("residual_sign", "double q = pt[v] - pd[v];", "double q = pd[v] - pt[v];", PINS[1:2]),
-    ("replacement_from_target", "double q = pt[v] - pd[v];", "double q = pt[v];", PINS[1:2]),
+    ("residual_sign", "      double q = pt[v] - pd[v];\n", "      double q = pd[v] - pt[v];\n", PINS[1:2]),
+    ("residual_support_without_floor", "if (q <= EARS_ORACLE_RESIDUAL_FLOOR * (pt[v] + pd[v])) q = 0.0;", "", PINS[1:2]),
+    ("replacement_from_target", "      double q = pt[v] - pd[v];\n", "      double q = pt[v];\n", PINS[1:2]),
     ("bonus_row", "const void* row = row_ptr(target_rows, dtype, K, V);",
      "const void* row = row_ptr(target_rows, dtype, K - 1, V);", PINS[1:2]),
     ("bonus_ignores_temperature", "top2_push(&top, l / T + ears_oracle_gumbel", "top2_push(&top, l + ears_oracle_gumbel", PINS[1:2]),

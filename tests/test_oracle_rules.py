@@ -430,6 +430,28 @@ def test_residual_law_and_empty_residual_fallback(oracle):
 
 
 # ----------------------------------------------- alternative uncertainty measure (Section 5)
+def test_residual_support_ignores_rounding_noise(oracle):
+    """Target and draft put 1 - 3.5e-13 on entry 0 and differ only far down the tail, so that
+    p_t(0) - p_d(0) is about +2e-15, i.e. a few units in the last place of two numbers near 1.  That
+    is the softmax's own rounding noise, not residual mass: the replacement token has to come from
+    the entries where the target really is more likely (here only entry 1, with q ~ 4e-15)."""
+    T = 1.0
+    target = np.array([30.0, 1.0, 0.0, -1.0, -2.0, -3.0], dtype=np.float32)
+    draft = np.array([30.0, 1.0 - 2.0 ** -6, 2.0 ** -4, -1.0, -2.0, -3.0], dtype=np.float32)
+    pt, pd = softmax64(target, T), softmax64(draft, T)
+    rel = (pt - pd) / (pt + pd)
+    # the premise: entry 1 carries real residual mass, entry 2 none, and entries 0, 3, 4, 5 (equal
+    # logits in both rows) differ only through the two normalisers, by ~1e-15 relative
+    assert rel[1] > 1e-3 and rel[2] < 0 and ((rel[[0, 3, 4, 5]] > 0) & (rel[[0, 3, 4, 5]] < 1e-14)).all()
+    assert pt[0] - pd[0] > 0.3 * (pt[1] - pd[1])       # unfloored, entry 0 would win often
+    B = 3000
+    r = oracle.verify(np.stack([target] * 2)[None].repeat(B, 0), draft[None, None].repeat(B, 0),
+                      np.full((B, 1), 2, dtype=np.int32), T, 0.0, 11, nthreads=4)
+    rejected = r.accept_len == 0
+    assert rejected.sum() > 2900          # P_d(x) is below the division guard: R = P_t(x) / 1e-10 ~ 1e-3
+    assert (r.tokens[rejected, 0] == 1).all()
+
+
 def test_entropy_against_library(oracle):
     rng = np.random.default_rng(50)
     for V in (2, 17, 5000):
