@@ -1,0 +1,78 @@
+"""A seeded random sweep of the verification step against the CPU oracle: a few hundred small
+problems across shapes, storage types, temperatures, tolerances, uncertainty measures, masks,
+sequence ids, ragged batches and deliberately ill-conditioned rows (sharply peaked, nearly
+identical target and draft rows with arbitrary draft tokens).  Longer runs of the same generator
+(10^5 problems) found the two corner cases that test_gpu_parity.py now pins."""
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from parity_util import compare
+
+pytestmark = pytest.mark.gpu
+
+NTHREADS = min(16, os.cpu_count() or 1)
+
+
+def _check(ears, oracle, inputs, target, draft, tokens, T, beta, seed, unc, ids, desc):
+    ids_dev = None if ids is None else torch.as_tensor(ids, device="cuda")
+    out = ears.ears_verify_ex(target, draft, tokens, temperature=T, beta=beta, seed=seed, seq_ids=ids_dev,
+                              uncertainty=unc, want_stats=True, want_path=True)
+    torch.cuda.synchronize()
+    ora = oracle.verify(inputs.logits_to_numpy(target), inputs.logits_to_numpy(draft),
+                        tokens.cpu().numpy(), float(np.float32(T)), float(np.float32(beta)), seed,
+                        seq_ids=ids, nthreads=NTHREADS, uncertainty=unc)
+    try:
+        rep = compare(ora, out["accept_len"].cpu().numpy(), out["tokens"].cpu().numpy(),
+                      out["stats"].cpu().numpy(), out["path"].cpu().numpy(), None, target.shape[1] - 1,
+                      1e-5, tokens.cpu().numpy(), target.shape[-1], unc_is_maxprob=(unc == 0))
+    except AssertionError as e:
+        raise AssertionError("%s: %s" % (desc, e))
+    return rep
+
+
+def test_random_problems(oracle):
+    import paper_2512_13194_amd as ears
+    from paper_2512_13194_amd import inputs
+    ears.lib()
+    print("random sweep", flush=True)
+    rng = np.random.default_rng(20240607)
+    exempt = 0
+    for case in range(240):
+        B = int(rng.choice([1, 2, 7, 33, 130]))
+        K = int(rng.choice([1, 2, 4, 8, 11]))
+        V = int(rng.choice([1, 2, 5, 17, 100, 1000, 8191, 8193, 32000]))
+        dtype = torch.bfloat16 if rng.random() < 0.6 else torch.float32
+        T = float(rng.choice([0.1, 0.5, 0.9, 1.0, 2.0]))
+        beta = float(rng.choice([0.0, 0.1, 0.5, 1.0]))
+        unc = int(rng.random() < 0.3)
+        seed = int(rng.integers(0, 2 ** 63))
+        ds = int(rng.integers(0, 2 ** 31))
+        kind = int(rng.integers(0, 3))
+        desc = dict(case=case, B=B, K=K, V=V, dtype=str(dtype), T=T, beta=beta, unc=unc, kind=kind)
+        g = torch.Generator(device="cuda").manual_seed(ds)
+        if kind == 0:      # the workloads' recipe
+            batch = inputs.make_rect(B, K, V, dtype, T=T, data_seed=ds, draft_noise=float(rng.choice([0.0, 0.5, 2.0])),
+                                     peaked_frac=float(rng.choice([0.0, 0.3])), device="cuda")
+            target, draft, tokens = batch.target, batch.draft, batch.tokens
+        elif kind == 1:    # ill-conditioned: peaked, nearly identical rows, tokens not drawn from the draft
+            batch = inputs.make_rect(B, K, V, dtype, T=T, data_seed=ds, draft_noise=float(rng.choice([0.0, 1e-3, 1e-2])),
+                                     peaked_frac=1.0, peaked_sigma=float(rng.choice([6.0, 20.0])), device="cuda")
+            target, draft = batch.target, batch.draft
+            tokens = torch.randint(0, V, (B, K), generator=g, device="cuda", dtype=torch.int32)
+        else:              # quantised logits (many equal values) with a masked vocabulary
+            t = torch.round(torch.randn(B, K + 1, V, generator=g, device="cuda") * 6) / 2
+            d = torch.round((t[:, :K] + torch.randn(B, K, V, generator=g, device="cuda")) * 2) / 2
+            if V > 4:
+                mask = torch.rand(V, generator=g, device="cuda") < float(rng.choice([0.3, 0.95]))
+                mask[int(rng.integers(0, V))] = False
+                t[:, :, mask] = float("-inf")
+                d[:, :, mask] = float("-inf")
+            target, draft = t.to(dtype).contiguous(), d.to(dtype).contiguous()
+            tokens = torch.randint(0, V, (B, K), generator=g, device="cuda", dtype=torch.int32)
+        ids = rng.integers(0, 2 ** 50, size=B).astype(np.int64) if rng.random() < 0.5 else None
+        rep = _check(ears, oracle, inputs, target, draft, tokens, T, beta, seed, unc, ids, desc)
+        exempt += rep.exempt_decisions + rep.exempt_tokens
+    assert exempt <= 1
