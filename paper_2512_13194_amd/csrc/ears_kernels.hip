@@ -10,7 +10,12 @@
 //                                       filter's prologue
 //
 // The path is bound by HBM bandwidth (every needed row is read once, plus one re-read of the row
-// pair the sampler needs), so there is no matrix-core work here.
+// pair the sampler needs): no matrix-core work in it.
+//
+// Beside it: greedy.h (temperature -> 0: arg-max of the target rows and a prefix scan), lm_head.h
+// (the vocabulary projection on the matrix cores with a statistics epilogue, and the import of
+// producer-side statistics into a verification workspace), and single_row_stats_kernel in
+// row_stats.h (the statistics pass over one matrix on its own).
 #include <hip/hip_runtime.h>
 
 #include <cmath>
