@@ -9,7 +9,9 @@ from .ears_oracle import (  # noqa: F401
     OracleResult,
     UNC_ENTROPY,
     UNC_MAXPROB,
+    UNC_VARIANCE,
     entropy,
+    variance,
     accept_uniform,
     build,
     gumbel,

@@ -135,6 +135,14 @@ double ears_oracle_entropy(const double* p, int V) {
   return H;
 }
 
+/* Total variance of the one-hot outcome X ~ p: the trace of its covariance matrix, sum_v of the
+ * Bernoulli variances p_v (1 - p_v) (= 1 - sum_v p_v^2, the Gini-Simpson index). */
+double ears_oracle_variance(const double* p, int V) {
+  double G = 0.0;
+  for (int v = 0; v < V; ++v) G += p[v] * (1.0 - p[v]);
+  return G;
+}
+
 int ears_oracle_verify_seq(const void* target_rows, const void* draft_rows, const int32_t* tokens,
                            int dtype, int K, int V, double T, double beta, int unc_mode, uint64_t seed,
                            uint64_t seq_id, int32_t* accept_len, int32_t* out_tokens, double* diag,
@@ -161,9 +169,11 @@ int ears_oracle_verify_seq(const void* target_rows, const void* draft_rows, cons
     double U = ears_oracle_accept_uniform(seed, seq_id, (uint32_t)i);
     /* step 4: uncertainty 1 - max P_t and tolerance beta * uncertainty (Section 3.2); the
      * alternative measure (Section 5, "distribution entropy") is the Shannon entropy of P_t
-     * divided by its largest possible value log V */
+     * divided by its largest possible value log V; the other one it names ("variance") is taken
+     * as the total variance of the one-hot outcome, sum_v P_t(v) (1 - P_t(v)) */
     double unc = 1.0 - maxpt;
     if (unc_mode == EARS_ORACLE_UNC_ENTROPY) unc = (V > 1) ? ears_oracle_entropy(pt, V) / log((double)V) : 0.0;
+    if (unc_mode == EARS_ORACLE_UNC_VARIANCE) unc = ears_oracle_variance(pt, V);
     double tol = beta * unc;
     /* threshold clamp of Section 3.3 item 2 */
     double thr = U - tol;

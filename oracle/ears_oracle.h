@@ -39,7 +39,8 @@ extern "C" {
  *   0 m_t   max target logit                      5 P_d(x)  draft probability of the draft token
  *   1 Z_t   sum_v exp((l_t[v]-m_t)/T)             6 unc     1 - max_v P_t(v)   (Section 3.2)
  *   2 P_t(x) target probability of draft token    7 R       P_t(x) / max(P_d(x), 1e-10)
- *     (or H(P_t)/log V when the entropy measure is selected)
+ *     (or H(P_t)/log V, or sum_v P_t(v)(1 - P_t(v)), when the entropy or the variance measure
+ *     is selected)
  *   3 m_d   max draft logit                       8 U       acceptance uniform in [0,1)
  *   4 Z_d   draft sum-exp                         9 thr     max(U - beta*unc, 0)   (Section 3.3)
  */
@@ -51,8 +52,10 @@ extern "C" {
  */
 #define EARS_ORACLE_NSAMP 4
 
-/* uncertainty measure that scales the tolerance: the paper's 1 - max P_t (Section 3.2), or the
- * normalised Shannon entropy H(P_t) / log V (the "distribution entropy" of Section 5) */
+/* uncertainty measure that scales the tolerance: the paper's 1 - max P_t (Section 3.2), the
+ * normalised Shannon entropy H(P_t) / log V (the "distribution entropy" of Section 5), or the
+ * total variance sum_v P_t(v) (1 - P_t(v)) of the one-hot outcome (the "variance" of Section 5,
+ * which the paper does not define further) */
 /* Support of the residual distribution norm(max(0, p_t - p_d)): an entry belongs to it when
  * p_t(v) - p_d(v) exceeds this fraction of p_t(v) + p_d(v).  2^-40 is far above the rounding noise
  * of an fp64 softmax (about 2^-50 relative) and far below anything a sampler can resolve (it
@@ -62,6 +65,7 @@ extern "C" {
 
 #define EARS_ORACLE_UNC_MAXPROB 0
 #define EARS_ORACLE_UNC_ENTROPY 1
+#define EARS_ORACLE_UNC_VARIANCE 2
 
 /* One Philox4x32-10 block: 10 rounds on a 128-bit counter with a 64-bit key. */
 void ears_oracle_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4]);
@@ -92,6 +96,8 @@ double ears_oracle_softmax(const void* row, int dtype, int V, double T, double* 
 
 /* Shannon entropy -sum p log p (nats) of a probability vector. */
 double ears_oracle_entropy(const double* p, int V);
+/* Total variance sum_v p_v (1 - p_v) of the one-hot outcome drawn from p. */
+double ears_oracle_variance(const double* p, int V);
 
 /* Verify one sequence.
  *   target_rows [K+1, V], draft_rows [K, V] row-major logits of type dtype

@@ -68,6 +68,8 @@ def _load():
     lib.ears_oracle_softmax.restype = c.c_double
     lib.ears_oracle_entropy.argtypes = [c.c_void_p, c.c_int]
     lib.ears_oracle_entropy.restype = c.c_double
+    lib.ears_oracle_variance.argtypes = [c.c_void_p, c.c_int]
+    lib.ears_oracle_variance.restype = c.c_double
     lib.ears_oracle_verify.argtypes = [
         c.c_void_p, c.c_void_p, c.c_void_p, c.c_int, c.c_int, c.c_int, c.c_int, c.c_double,
         c.c_double, c.c_int, c.c_uint64, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p,
@@ -155,13 +157,19 @@ class OracleResult:
         return self.diag[..., DIAG_NAMES.index(name)]
 
 
-UNC_MAXPROB, UNC_ENTROPY = 0, 1
+UNC_MAXPROB, UNC_ENTROPY, UNC_VARIANCE = 0, 1, 2
 
 
 def entropy(p: np.ndarray) -> float:
     """Shannon entropy (nats) of a float64 probability vector."""
     p = np.ascontiguousarray(p, dtype=np.float64)
     return float(_load().ears_oracle_entropy(_ptr(p), p.shape[0]))
+
+
+def variance(p: np.ndarray) -> float:
+    """Total variance sum_v p_v (1 - p_v) of the one-hot outcome drawn from p (float64 vector)."""
+    p = np.ascontiguousarray(p, dtype=np.float64)
+    return float(_load().ears_oracle_variance(_ptr(p), p.shape[0]))
 
 
 def verify(target: np.ndarray, draft: np.ndarray, tokens: np.ndarray, T: float, beta: float,

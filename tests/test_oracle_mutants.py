@@ -43,6 +43,8 @@ MUTANTS = [
     # not planted: `s >= t->best` in the Gumbel arg-max (ties to the highest index).  Two entries tie
     # only if their 40-bit noise values and residuals coincide; no input of feasible size shows it.
     ("entropy_in_bits", "H -= p[v] * log(p[v]);", "H -= p[v] * log2(p[v]);", PINS[1:2]),
+    ("variance_is_sum_of_squares", "G += p[v] * (1.0 - p[v]);", "G += p[v] * p[v];", PINS[1:2]),
+    ("variance_measure_not_selected", "    if (unc_mode == EARS_ORACLE_UNC_VARIANCE) unc = ears_oracle_variance(pt, V);\n", "", PINS[1:2]),
     ("ragged_target_rows", "row_ptr(target, dtype, r0 + b, V), row_ptr(draft, dtype, r0, V), tokens + r0",
      "row_ptr(target, dtype, r0, V), row_ptr(draft, dtype, r0, V), tokens + r0", PINS[1:2]),
     ("greedy_ties_to_highest_index", "    if (x > bv) {", "    if (x >= bv) {", PINS[2:3]),

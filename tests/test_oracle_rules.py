@@ -511,3 +511,78 @@ def test_entropy_uncertainty_limits_and_acceptance_rate(oracle):
     # and it differs from the max-prob tolerance
     want_mp = min(1.0, pt[x] / pd[x] + beta * (1.0 - pt.max()))
     assert stats.binomtest(int((r.accept_len == 1).sum()), N, want_mp).pvalue < 1e-6
+
+
+def test_variance_against_its_definition(oracle):
+    # closed forms: uniform 1 - 1/V, a point mass 0, two points 2 p (1 - p)
+    assert oracle.variance(np.full(64, 1 / 64)) == pytest.approx(1 - 1 / 64, rel=1e-14)
+    assert oracle.variance(np.array([0.0, 1.0, 0.0])) == 0.0
+    assert oracle.variance(np.array([0.3, 0.7])) == pytest.approx(2 * 0.3 * 0.7, rel=1e-14)
+    rng = np.random.default_rng(60)
+    for V in (2, 17, 5000):
+        p = rng.dirichlet(np.ones(V) * 0.3)
+        assert oracle.variance(p) == pytest.approx(1.0 - float(np.dot(p, p)), rel=1e-11, abs=1e-15)
+    # the name: trace of the covariance matrix of one-hot draws from p
+    p = np.array([0.5, 0.2, 0.15, 0.1, 0.05])
+    onehot = rng.multinomial(1, p, size=400000).astype(np.float64)
+    assert float(np.trace(np.cov(onehot.T))) == pytest.approx(oracle.variance(p), rel=5e-3)
+
+
+def test_variance_uncertainty_hand_worked(oracle):
+    # P_t = (1/2, 1/4, 1/8, 1/8): sum of squares 11/32, uncertainty 21/32 = 0.65625 (1 - max P_t is
+    # 1/2, the entropy measure 7/8).  P_d uniform, x = 2: R = 1/2.  beta = 0.4: tolerance 0.2625,
+    # so U <= 0.5 primary, 0.5 < U <= 0.7625 pardon, else reject.
+    T, beta, seed = 1.0, 0.4, 321
+    lt = logits_from_probs([0.5, 0.25, 0.125, 0.125], T)
+    ld = logits_from_probs([0.25] * 4, T)
+    target, draft = np.stack([lt, lt])[None], ld[None, None]
+    tokens = np.array([[2]], dtype=np.int32)
+    for lo, hi, want in [(0.0, 0.45, 1), (0.55, 0.65, 2), (0.71, 0.75, 2), (0.78, 0.84, 0), (0.87, 1.0, 0)]:
+        s = _find_seq(oracle, seed, 0, lo, hi)
+        r = oracle.verify(target, draft, tokens, T, beta, seed, seq_ids=np.array([s]),
+                          uncertainty=oracle.UNC_VARIANCE)
+        assert r.d("unc")[0, 0] == pytest.approx(0.65625, rel=1e-6)
+        U = r.d("U")[0, 0]
+        assert r.d("thr")[0, 0] == pytest.approx(max(U - 0.2625, 0.0), abs=1e-6)
+        assert r.path[0, 0] == want
+    # the same uniforms under the other two measures: 0.71..0.75 is beyond 1 - max P_t's reach,
+    # 0.78..0.84 within the entropy measure's
+    s = _find_seq(oracle, seed, 0, 0.71, 0.75)
+    assert oracle.verify(target, draft, tokens, T, beta, seed, seq_ids=np.array([s])).path[0, 0] == 0
+    s = _find_seq(oracle, seed, 0, 0.78, 0.84)
+    assert oracle.verify(target, draft, tokens, T, beta, seed, seq_ids=np.array([s]),
+                         uncertainty=oracle.UNC_ENTROPY).path[0, 0] == 2
+
+
+def test_variance_uncertainty_limits_order_and_acceptance_rate(oracle):
+    rng = np.random.default_rng(61)
+    V, N, T, beta = 8, 20000, 0.8, 0.6
+    flat = np.zeros(V, dtype=np.float32)
+    peaked = np.array([40.0] + [0.0] * (V - 1), dtype=np.float32)
+    for row, want in ((flat, 1.0 - 1.0 / V), (peaked, 0.0)):
+        r = oracle.verify(np.stack([row, row])[None], row[None, None], np.array([[1]], dtype=np.int32),
+                          T, beta, 1, uncertainty=oracle.UNC_VARIANCE)
+        assert r.d("unc")[0, 0] == pytest.approx(want, abs=1e-12)
+    # sum p^2 <= max p: never below the paper's measure, never above 1 - 1/V
+    rows = (rng.standard_normal((50, 2, 33)) * rng.uniform(0.2, 6.0, (50, 1, 1))).astype(np.float32)
+    tok = rng.integers(0, 33, (50, 1)).astype(np.int32)
+    r_var = oracle.verify(rows, rows[:, :1], tok, T, beta, 5, uncertainty=oracle.UNC_VARIANCE)
+    r_max = oracle.verify(rows, rows[:, :1], tok, T, beta, 5)
+    assert (r_var.d("unc") >= r_max.d("unc") - 1e-15).all()
+    assert (r_var.d("unc") <= 1.0 - 1.0 / 33 + 1e-15).all()
+    assert (r_var.d("unc") > r_max.d("unc") + 1e-3).any()
+    # acceptance probability min(1, R + beta (1 - sum p_t^2)) for a fixed token
+    lt = (rng.standard_normal(V) * 1.5).astype(np.float32)
+    ld = (lt + rng.standard_normal(V)).astype(np.float32)
+    pt, pd = softmax64(lt, T), softmax64(ld, T)
+    tol = beta * (1.0 - float(np.dot(pt, pt)))
+    target = np.ascontiguousarray(np.broadcast_to(lt, (N, 2, V)))
+    draft = np.ascontiguousarray(np.broadcast_to(ld, (N, 1, V)))
+    x = int(np.argmin(pt / pd))
+    r = oracle.verify(target, draft, np.full((N, 1), x, dtype=np.int32), T, beta, 78, nthreads=4,
+                      uncertainty=oracle.UNC_VARIANCE)
+    want = min(1.0, pt[x] / pd[x] + tol)
+    assert want < 1.0
+    assert stats.binomtest(int((r.accept_len == 1).sum()), N, want).pvalue > 1e-4
+    want_mp = min(1.0, pt[x] / pd[x] + beta * (1.0 - pt.max()))
+    assert stats.binomtest(int((r.accept_len == 1).sum()), N, want_mp).pvalue < 1e-6
