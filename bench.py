@@ -170,6 +170,10 @@ def main() -> int:
         batch.target, batch.draft, batch.tokens, temperature=T, beta=betas[1], seed=seed0,
         uncertainty=ears.EARS_UNCERTAINTY_ENTROPY, workspace=ws, out_accept_len=acc,
         out_tokens=tok.view(-1)))
+    var_ms = timed_ms(lambda: ears.ears_verify_ex(
+        batch.target, batch.draft, batch.tokens, temperature=T, beta=betas[1], seed=seed0,
+        uncertainty=ears.EARS_UNCERTAINTY_VARIANCE, workspace=ws, out_accept_len=acc,
+        out_tokens=tok.view(-1)))
     greedy_tokens = batch.target[:, :K].float().argmax(-1).to(torch.int32)
     greedy_tokens[::2, K // 2] = 0        # half of the sequences stop in the middle
     greedy_ms = timed_ms(lambda: ears.ears_verify_greedy(
@@ -177,6 +181,7 @@ def main() -> int:
     greedy_bytes = B * (K + 1) * V * esz
     other_paths = {
         "entropy_uncertainty": {"ms_per_call": ent_ms, "positions_per_s": B * K / (ent_ms * 1e-3)},
+        "variance_uncertainty": {"ms_per_call": var_ms, "positions_per_s": B * K / (var_ms * 1e-3)},
         "greedy_temperature_0": {"ms_per_call": greedy_ms,
                                  "positions_per_s": B * K / (greedy_ms * 1e-3),
                                  "algorithmic_bytes": greedy_bytes,

@@ -74,12 +74,15 @@ enum {
 };
 
 /* Uncertainty measure that scales the tolerance.  MAXPROB is the paper's 1 - max_v p_t(v)
- * (Section 3.2).  ENTROPY is the normalised Shannon entropy H(p_t) / log V of the same
- * distribution, one of the "more refined uncertainty measures" the paper's Section 5 names; it
- * comes out of the same single pass over the row. */
+ * (Section 3.2).  The other two are the "more refined uncertainty measures" the paper's Section 5
+ * names without formulas: ENTROPY is the normalised Shannon entropy H(p_t) / log V, VARIANCE the
+ * total variance sum_v p_t(v) (1 - p_t(v)) = 1 - sum_v p_t(v)^2 of the one-hot outcome drawn from
+ * p_t (in [0, 1 - 1/V], never below the MAXPROB measure).  Each comes out of the same single pass
+ * over the row. */
 typedef enum ears_uncertainty {
   EARS_UNCERTAINTY_MAXPROB = 0,
-  EARS_UNCERTAINTY_ENTROPY = 1
+  EARS_UNCERTAINTY_ENTROPY = 1,
+  EARS_UNCERTAINTY_VARIANCE = 2
 } ears_uncertainty;
 
 /* Number of doubles per (sequence, position) in `out_stats`:
@@ -237,7 +240,9 @@ int ears_row_stats(int dtype, const void* logits, int64_t rows, int V, float tem
  * same temperature(s)) completes the step without the statistics pass.
  *   target_row_max / target_row_sumexp   [total_draft_rows + B], packed like the target rows
  *   target_row_entropy                   same shape, or NULL; required before a DECIDE stage
- *                                        with EARS_UNCERTAINTY_ENTROPY
+ *                                        with EARS_UNCERTAINTY_ENTROPY (the VARIANCE measure is
+ *                                        not carried by imported statistics: it needs the STATS
+ *                                        stage of ears_verify_ex)
  *   draft_row_max / draft_row_sumexp     [total_draft_rows]
  * Other arguments as for ears_verify_ex. */
 int ears_import_stats(int dtype, const void* target_logits, const void* draft_logits,

@@ -16,6 +16,7 @@ from .binding import (  # noqa: F401
     EARS_STAGE_STATS,
     EARS_UNCERTAINTY_ENTROPY,
     EARS_UNCERTAINTY_MAXPROB,
+    EARS_UNCERTAINTY_VARIANCE,
     STAT_NAMES,
     EarsError,
     ears_bench_copy,

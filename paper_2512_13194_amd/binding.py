@@ -20,7 +20,7 @@ EARS_ERR_NULL, EARS_ERR_SHAPE, EARS_ERR_PARAM, EARS_ERR_ALIGN = 1, 2, 3, 4
 EARS_ERR_DTYPE, EARS_ERR_WORKSPACE, EARS_ERR_HIP = 5, 6, 7
 EARS_F32, EARS_BF16 = 0, 1
 EARS_STAGE_STATS, EARS_STAGE_DECIDE, EARS_STAGE_SAMPLE, EARS_STAGE_ALL = 1, 2, 4, 7
-EARS_UNCERTAINTY_MAXPROB, EARS_UNCERTAINTY_ENTROPY = 0, 1
+EARS_UNCERTAINTY_MAXPROB, EARS_UNCERTAINTY_ENTROPY, EARS_UNCERTAINTY_VARIANCE = 0, 1, 2
 EARS_NSTATS = 10
 STAT_NAMES = ("m_t", "Z_t", "P_t_x", "m_d", "Z_d", "P_d_x", "unc", "R", "U", "thr")
 

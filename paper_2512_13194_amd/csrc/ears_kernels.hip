@@ -121,14 +121,21 @@ static int launch(Problem p, int stages, hipStream_t stream) {
   p.decide_fused = fused ? 1 : 0;
   if (stats) {
     const dim3 grid((unsigned)p.R), block(kBlock);
-    if (fused && p.unc_mode)
-      hipLaunchKernelGGL((row_stats_kernel<DT, 4, true, true>), grid, block, 0, stream, p);
-    else if (fused)
-      hipLaunchKernelGGL((row_stats_kernel<DT, 4, true, false>), grid, block, 0, stream, p);
-    else if (p.unc_mode)
-      hipLaunchKernelGGL((row_stats_kernel<DT, 4, false, true>), grid, block, 0, stream, p);
-    else
-      hipLaunchKernelGGL((row_stats_kernel<DT, 4, false, false>), grid, block, 0, stream, p);
+    if (fused) {
+      if (p.unc_mode == EARS_UNCERTAINTY_ENTROPY)
+        hipLaunchKernelGGL((row_stats_kernel<DT, 4, true, kMeasureEntropy>), grid, block, 0, stream, p);
+      else if (p.unc_mode == EARS_UNCERTAINTY_VARIANCE)
+        hipLaunchKernelGGL((row_stats_kernel<DT, 4, true, kMeasureVariance>), grid, block, 0, stream, p);
+      else
+        hipLaunchKernelGGL((row_stats_kernel<DT, 4, true, kMeasureNone>), grid, block, 0, stream, p);
+    } else {
+      if (p.unc_mode == EARS_UNCERTAINTY_ENTROPY)
+        hipLaunchKernelGGL((row_stats_kernel<DT, 4, false, kMeasureEntropy>), grid, block, 0, stream, p);
+      else if (p.unc_mode == EARS_UNCERTAINTY_VARIANCE)
+        hipLaunchKernelGGL((row_stats_kernel<DT, 4, false, kMeasureVariance>), grid, block, 0, stream, p);
+      else
+        hipLaunchKernelGGL((row_stats_kernel<DT, 4, false, kMeasureNone>), grid, block, 0, stream, p);
+    }
   }
   if (decide && !fused) {
     hipLaunchKernelGGL(decide_kernel, dim3((unsigned)((p.B + kWavesPerBlock - 1) / kWavesPerBlock)),
@@ -206,7 +213,8 @@ int ears_verify_ex(int dtype, const void* target_logits, const void* draft_logit
                           beta_per_seq, seq_ids, workspace, workspace_bytes, stages, out_accept_len,
                           out_tokens, out_stats, out_path, status_word, &lay);
   if (rc != EARS_OK) return rc;
-  if (uncertainty != EARS_UNCERTAINTY_MAXPROB && uncertainty != EARS_UNCERTAINTY_ENTROPY)
+  if (uncertainty != EARS_UNCERTAINTY_MAXPROB && uncertainty != EARS_UNCERTAINTY_ENTROPY &&
+      uncertainty != EARS_UNCERTAINTY_VARIANCE)
     return EARS_ERR_PARAM;
   Problem p;
   p.target = target_logits;

@@ -23,11 +23,16 @@ namespace ears {
 // (Section 3.3 item 1: the maximum is cached, the row is never re-scanned for it).
 // =================================================================================================
 //
-// With kEntropy the lane also keeps W = sum e*y over the same terms, e = exp2(y),
-// y = l*c - fl(m*c) (clamped at -126 so that a masked entry contributes 0 * finite), which
-// rescales as W <- f*(W + d*S) when the offset moves by d (f = 2^d).  The Shannon entropy of the
-// row is then H = ln Z - ln 2 * W/S, one more FMA and one max per element.
-template <int N, bool kEntropy>
+// A second running sum W serves the alternative uncertainty measures (paper Section 5):
+//   kMeasureEntropy   W = sum e*y over the same terms, e = exp2(y), y = l*c - fl(m*c) (clamped at
+//                     -126 so that a masked entry contributes 0 * finite); it rescales as
+//                     W <- f*(W + d*S) when the offset moves by d (f = 2^d); the Shannon entropy of
+//                     the row is H = ln Z - ln 2 * W/S: one more FMA and one max per element;
+//   kMeasureVariance  W = sum e*e, which rescales as W <- f*f*W; sum_v p_v^2 = W/S^2 and the total
+//                     variance of the one-hot outcome is 1 - W/S^2: one more FMA per element.
+enum { kMeasureNone = 0, kMeasureEntropy = 1, kMeasureVariance = 2 };
+
+template <int N, int kMeasure>
 __device__ __forceinline__ void accumulate(const float (&f)[N], float c, float& m_run, float& mc,
                                            float& S, float& W) {
   float cm = f[0];
@@ -41,7 +46,8 @@ __device__ __forceinline__ void accumulate(const float (&f)[N], float c, float& 
     } else {
       const float d = mc - mc_new;
       const float scale = __builtin_amdgcn_exp2f(d);
-      if (kEntropy) W = scale * fmaf(d, S, W);
+      if (kMeasure == kMeasureEntropy) W = scale * fmaf(d, S, W);
+      if (kMeasure == kMeasureVariance) W = (scale * scale) * W;
       S *= scale;
     }
     m_run = cm;
@@ -52,18 +58,19 @@ __device__ __forceinline__ void accumulate(const float (&f)[N], float c, float& 
 #pragma unroll
   for (int j = 0; j < N; ++j) {
     float y = fmaf(f[j], c, -mc);
-    if (kEntropy) y = fmaxf(y, -126.0f);
+    if (kMeasure == kMeasureEntropy) y = fmaxf(y, -126.0f);
     const float e = __builtin_amdgcn_exp2f(y);
     s[j & 3] += e;
-    if (kEntropy) w[j & 3] = fmaf(e, y, w[j & 3]);
+    if (kMeasure == kMeasureEntropy) w[j & 3] = fmaf(e, y, w[j & 3]);
+    if (kMeasure == kMeasureVariance) w[j & 3] = fmaf(e, e, w[j & 3]);
   }
   S += (s[0] + s[1]) + (s[2] + s[3]);
-  if (kEntropy) W += (w[0] + w[1]) + (w[2] + w[3]);
+  if (kMeasure != kMeasureNone) W += (w[0] + w[1]) + (w[2] + w[3]);
 }
 
-// Streams one row; on return thread 0 holds the row maximum M, Z = sum exp((l - M)/T) and, with
-// kEntropy, the Shannon entropy H (nats) of softmax(l/T).
-template <typename DT, int kUnroll, bool kEntropy>
+// Streams one row; on return thread 0 holds the row maximum M, Z = sum exp((l - M)/T) and in
+// H_out the Shannon entropy (nats) or the total variance of softmax(l/T), whichever kMeasure names.
+template <typename DT, int kUnroll, int kMeasure>
 __device__ __forceinline__ void row_pass(const typename DT::storage* base, int V, float c,
                                          float* sh_m, double* sh_s, float& M_out, double& Z_out,
                                          double& H_out) {
@@ -81,7 +88,7 @@ __device__ __forceinline__ void row_pass(const typename DT::storage* base, int V
   const int ntail = V - tail0;
   if (tid < head + ntail) {
     float f[1] = {DT::load(base, tid < head ? tid : tail0 + (tid - head))};
-    accumulate<1, kEntropy>(f, c, m_run, mc, S, W);
+    accumulate<1, kMeasure>(f, c, m_run, mc, S, W);
   }
 
   const uint4* vp = reinterpret_cast<const uint4*>(base + head);
@@ -100,7 +107,7 @@ __device__ __forceinline__ void row_pass(const typename DT::storage* base, int V
 #pragma unroll
       for (int j = 0; j < kPer; ++j) f[u * kPer + j] = g[j];
     }
-    accumulate<kUnroll * kPer, kEntropy>(f, c, m_run, mc, S, W);
+    accumulate<kUnroll * kPer, kMeasure>(f, c, m_run, mc, S, W);
   }
 
   // merge the lanes of the workgroup
@@ -116,10 +123,12 @@ __device__ __forceinline__ void row_pass(const typename DT::storage* base, int V
   const float scale = (m_run == -INFINITY) ? 0.0f : __builtin_amdgcn_exp2f(mc - Mc);
   const double part = wave_sum((double)S * (double)scale);
   double wpart = 0.0;
-  if (kEntropy) wpart = wave_sum((double)scale * ((double)W + (double)(mc - Mc) * (double)S));
+  if (kMeasure == kMeasureEntropy)
+    wpart = wave_sum((double)scale * ((double)W + (double)(mc - Mc) * (double)S));
+  if (kMeasure == kMeasureVariance) wpart = wave_sum(((double)scale * (double)scale) * (double)W);
   if (lane == 0) {
     sh_s[wave] = part;
-    if (kEntropy) sh_s[kWavesPerBlock + wave] = wpart;
+    if (kMeasure != kMeasureNone) sh_s[kWavesPerBlock + wave] = wpart;
   }
   __syncthreads();
   if (tid == 0) {
@@ -130,17 +139,18 @@ __device__ __forceinline__ void row_pass(const typename DT::storage* base, int V
     const double delta = (double)Mc - (double)M * (double)c;
     Z_out = Zp * exp2(delta);
     M_out = M;
-    if (kEntropy) {
+    if (kMeasure != kMeasureNone) {
 #pragma unroll
       for (int w = 0; w < kWavesPerBlock; ++w) Wp += sh_s[kWavesPerBlock + w];
-      // H = ln Z - ln 2 * sum p*y2; the offset's rounding shifts both terms equally, so the
-      // sums taken with fl(M*c) serve as they are
-      H_out = log(Zp) - 0.69314718055994530942 * (Wp / Zp);
+      // H = ln Z - ln 2 * sum p*y2, and sum p^2 = sum e^2 / (sum e)^2; the offset's rounding shifts
+      // or scales both terms equally, so the sums taken with fl(M*c) serve as they are
+      if (kMeasure == kMeasureEntropy) H_out = log(Zp) - 0.69314718055994530942 * (Wp / Zp);
+      if (kMeasure == kMeasureVariance) H_out = (Zp * Zp - Wp) / (Zp * Zp);
     }
   }
 }
 
-template <typename DT, int kUnroll, bool kDecide, bool kEntropy>
+template <typename DT, int kUnroll, bool kDecide, int kMeasure>
 __global__ __launch_bounds__(kBlock) void row_stats_kernel(Problem p) {
   using storage = typename DT::storage;
   __shared__ float sh_m[kWavesPerBlock];
@@ -169,8 +179,8 @@ __global__ __launch_bounds__(kBlock) void row_stats_kernel(Problem p) {
 
   float Mt = 0.0f, Md = 0.0f;
   double Zt = 0.0, Zd = 0.0, Ht = 0.0, Hd = 0.0;
-  row_pass<DT, kUnroll, kEntropy>(trow, V, c, sh_m, sh_s, Mt, Zt, Ht);
-  row_pass<DT, kUnroll, false>(drow, V, c, sh_m, sh_s, Md, Zd, Hd);
+  row_pass<DT, kUnroll, kMeasure>(trow, V, c, sh_m, sh_s, Mt, Zt, Ht);
+  row_pass<DT, kUnroll, kMeasureNone>(drow, V, c, sh_m, sh_s, Md, Zd, Hd);
 
   if (threadIdx.x == 0) {
     p.Z[2 * r] = Zt;
@@ -179,12 +189,12 @@ __global__ __launch_bounds__(kBlock) void row_stats_kernel(Problem p) {
     p.m[2 * r + 1] = Md;
     p.lx[2 * r] = lxt;
     p.lx[2 * r + 1] = lxd;
-    // uncertainty of the target distribution: 1 - max P_t = 1 - 1/Z_t, or H / log V
+    // uncertainty of the target distribution: 1 - max P_t = 1 - 1/Z_t, or H / log V, or the
+    // total variance 1 - sum P_t^2
     double unc = 1.0 - 1.0 / Zt;
-    if (kEntropy) {
-      unc = V > 1 ? fmin(fmax(Ht / log((double)V), 0.0), 1.0) : 0.0;
-      p.unc[r] = unc;
-    }
+    if (kMeasure == kMeasureEntropy) unc = V > 1 ? fmin(fmax(Ht / log((double)V), 0.0), 1.0) : 0.0;
+    if (kMeasure == kMeasureVariance) unc = fmin(fmax(Ht, 0.0), 1.0);
+    if (kMeasure != kMeasureNone) p.unc[r] = unc;
     if (kDecide)
       p.decisions[r] = decide_position(p, b, r, x, U, (double)Mt, Zt, (double)lxt, (double)Md, Zd,
                                        (double)lxd, unc);
@@ -206,6 +216,7 @@ struct RowStatsProblem {
 
 template <typename DT, int kUnroll, bool kEntropy>
 __global__ __launch_bounds__(kBlock) void single_row_stats_kernel(RowStatsProblem p) {
+  constexpr int kMeasure = kEntropy ? kMeasureEntropy : kMeasureNone;
   using storage = typename DT::storage;
   __shared__ float sh_m[kWavesPerBlock];
   __shared__ double sh_s[2 * kWavesPerBlock];
@@ -214,7 +225,7 @@ __global__ __launch_bounds__(kBlock) void single_row_stats_kernel(RowStatsProble
   const float c = (float)(kLog2e / (double)T);
   float M = 0.0f;
   double Z = 0.0, H = 0.0;
-  row_pass<DT, kUnroll, kEntropy>(static_cast<const storage*>(p.logits) + row * (int64_t)p.V, p.V,
+  row_pass<DT, kUnroll, kMeasure>(static_cast<const storage*>(p.logits) + row * (int64_t)p.V, p.V,
                                   c, sh_m, sh_s, M, Z, H);
   if (threadIdx.x == 0) {
     p.row_m[row] = M;

@@ -34,13 +34,15 @@ class EarsVerifier:
     (Section 3.2; its experiments use T = 0.9, beta = 0.1).  beta = 0 is standard speculative
     sampling.  `seed` fixes the whole noise stream: step t of sequence id s always sees the same
     random numbers, whatever slot of the batch the sequence occupies.  `uncertainty` selects what
-    scales the tolerance: "maxprob" (the paper's 1 - max P_target) or "entropy" (normalised
-    Shannon entropy, the refinement its Section 5 names).  temperature = 0 selects greedy
-    verification (accept while the draft token is the target arg-max): no draft logits, no noise.
+    scales the tolerance: "maxprob" (the paper's 1 - max P_target), or one of the refinements its
+    Section 5 names: "entropy" (normalised Shannon entropy) or "variance" (1 - sum P_target^2).
+    temperature = 0 selects greedy verification (accept while the draft token is the target
+    arg-max): no draft logits, no noise.
     """
 
     UNCERTAINTY = {"maxprob": binding.EARS_UNCERTAINTY_MAXPROB,
-                   "entropy": binding.EARS_UNCERTAINTY_ENTROPY}
+                   "entropy": binding.EARS_UNCERTAINTY_ENTROPY,
+                   "variance": binding.EARS_UNCERTAINTY_VARIANCE}
 
     def __init__(self, temperature: float = 0.9, beta: float = 0.1, seed: int = 0,
                  telemetry: bool = False, uncertainty: str = "maxprob"):

@@ -91,7 +91,7 @@ def test_ex_argument_errors(L):
     assert _ex(L, off=P, R=1, B=2) == b.EARS_ERR_SHAPE     # ragged: at least one row per sequence
     assert _ex(L, stages=0) == b.EARS_ERR_PARAM
     assert _ex(L, stages=8) == b.EARS_ERR_PARAM
-    assert _ex(L, unc=2) == b.EARS_ERR_PARAM
+    assert _ex(L, unc=3) == b.EARS_ERR_PARAM
     assert _ex(L, unc=-1) == b.EARS_ERR_PARAM
     assert _ex(L, T=0.0) == b.EARS_ERR_PARAM
     assert _ex(L, T=0.0, Ts=P, ws=None) == b.EARS_ERR_WORKSPACE   # per-sequence T: scalar ignored

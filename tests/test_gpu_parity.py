@@ -273,17 +273,25 @@ def test_stages_split_reuses_cached_statistics(ears, oracle):
     assert all(t[i, acc[i]] == -1 for i in range(12))
 
 
-# ------------------------------------------------- entropy-based uncertainty (Section 5 outlook)
+# ---------------------------------- entropy- and variance-based uncertainty (Section 5 outlook)
+MEASURES = ["entropy", "variance"]
+
+
+def _measure(ears, name):
+    return {"entropy": ears.EARS_UNCERTAINTY_ENTROPY, "variance": ears.EARS_UNCERTAINTY_VARIANCE}[name]
+
+
+@pytest.mark.parametrize("measure", MEASURES)
 @pytest.mark.parametrize("index", [0, 2])
-def test_entropy_uncertainty_workloads(ears, oracle, index):
+def test_alternative_uncertainty_workloads(ears, oracle, index, measure):
     from paper_2512_13194_amd import inputs
     cfg = inputs.CONFIGS[index]
     T = cfg["temperatures"][0]
     batch = inputs.make_config(index, T=T, device="cuda")
     for beta in (cfg["betas"][-1], 1.0):
-        _log("entropy workload %s T=%s beta=%s" % (cfg["name"], T, beta))
+        _log("%s workload %s T=%s beta=%s" % (measure, cfg["name"], T, beta))
         rep, ora, out = run_rect(ears, oracle, batch, T, beta, cfg["seed"],
-                                 uncertainty=ears.EARS_UNCERTAINTY_ENTROPY)
+                                 uncertainty=_measure(ears, measure))
         _log("  " + rep.line() + " mean_accept=%.3f" % ora.accept_len.mean())
         assert rep.exempt_decisions <= 1 and rep.exempt_tokens <= 1
         # the measure changes decisions: the run is not a replay of the max-probability one
@@ -296,25 +304,27 @@ def test_entropy_uncertainty_workloads(ears, oracle, index):
     (1, 1, 1, torch.float32), (3, 2, 8, torch.float32), (5, 3, 13, torch.bfloat16),
     (2, 4, 4099, torch.float32), (7, 8, 8192, torch.bfloat16), (2, 3, 65537, torch.bfloat16),
 ])
-def test_entropy_uncertainty_edge_shapes(ears, oracle, B, K, V, dtype):
+@pytest.mark.parametrize("measure", MEASURES)
+def test_alternative_uncertainty_edge_shapes(ears, oracle, B, K, V, dtype, measure):
     from paper_2512_13194_amd import inputs
-    _log("entropy edge B=%d K=%d V=%d %s" % (B, K, V, dtype))
+    _log("%s edge B=%d K=%d V=%d %s" % (measure, B, K, V, dtype))
     batch = inputs.make_rect(B, K, V, dtype, T=0.7, data_seed=B * 1000 + V + 1, draft_noise=1.0,
                              device="cuda")
-    rep, _, _ = run_rect(ears, oracle, batch, 0.7, 0.5, 21, uncertainty=ears.EARS_UNCERTAINTY_ENTROPY)
+    rep, _, _ = run_rect(ears, oracle, batch, 0.7, 0.5, 21, uncertainty=_measure(ears, measure))
     assert rep.exempt_decisions == 0 and rep.exempt_tokens == 0
 
 
-def test_entropy_uncertainty_masked_peaked_ragged_and_stages(ears, oracle):
+@pytest.mark.parametrize("measure", MEASURES)
+def test_alternative_uncertainty_masked_peaked_ragged_and_stages(ears, oracle, measure):
     from paper_2512_13194_amd import inputs
-    ENT = ears.EARS_UNCERTAINTY_ENTROPY
-    _log("entropy masked / peaked")
+    ENT = _measure(ears, measure)
+    _log("%s masked / peaked" % measure)
     batch = inputs.make_rect(16, 4, 5000, torch.bfloat16, T=1.0, data_seed=78, draft_noise=1.0,
                              peaked_frac=0.3, peaked_sigma=12.0, device="cuda")
     mask = torch.rand(5000, device="cuda") < 0.4
     batch.target[:, :, mask] = float("-inf")
     batch.draft[:, :, mask] = float("-inf")
-    # one target row with a single unmasked entry: entropy exactly 0
+    # one target row with a single unmasked entry: entropy and variance exactly 0
     batch.target[1, 0, :] = float("-inf")
     batch.target[1, 0, 17] = 3.0
     rep, ora, out = run_rect(ears, oracle, batch, 1.0, 0.6, 10, uncertainty=ENT)
@@ -322,12 +332,12 @@ def test_entropy_uncertainty_masked_peaked_ragged_and_stages(ears, oracle):
     # fp32 rounding of the single exp2 term bounds what the kernel can resolve
     assert abs(out["stats"][1 * 4 + 0, 6].item()) < 1e-7 and ora.diag[1, 0, 6] == 0.0
 
-    _log("entropy ragged")
+    _log("%s ragged" % measure)
     rb = inputs.make_ragged(37, 3001, torch.bfloat16, data_seed=83, device="cuda")
     rep, _, _ = run_ragged(ears, oracle, rb, 15, uncertainty=ENT)
     assert rep.exempt_decisions == 0 and rep.exempt_tokens == 0
 
-    _log("entropy stages")
+    _log("%s stages" % measure)
     kw = dict(temperature=1.0, beta=0.6, seed=10, uncertainty=ENT)
     a = ears.ears_verify_ex(batch.target, batch.draft, batch.tokens, stages=ears.EARS_STAGE_STATS, **kw)
     b = ears.ears_verify_ex(batch.target, batch.draft, batch.tokens,

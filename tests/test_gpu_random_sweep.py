@@ -48,6 +48,8 @@ def test_random_problems(oracle):
         T = float(rng.choice([0.1, 0.5, 0.9, 1.0, 2.0]))
         beta = float(rng.choice([0.0, 0.1, 0.5, 1.0]))
         unc = int(rng.random() < 0.3)
+        if unc and case % 2:
+            unc = 2    # the variance measure instead of the entropy measure
         seed = int(rng.integers(0, 2 ** 63))
         ds = int(rng.integers(0, 2 ** 31))
         kind = int(rng.integers(0, 3))

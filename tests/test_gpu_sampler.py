@@ -92,34 +92,36 @@ def test_uncertainty_rises_with_temperature(pkg):
     assert all(a < b for a, b in zip(means, means[1:]))
 
 
-def test_entropy_measure_through_the_verifier(pkg, oracle):
-    """The verifier's entropy option gives the oracle's decisions and tokens for the entropy-based
+@pytest.mark.parametrize("measure", ["entropy", "variance"])
+def test_alternative_measures_through_the_verifier(pkg, oracle, measure):
+    """The verifier's entropy / variance option gives the oracle's decisions and tokens for that
     tolerance, its telemetry counts the oracle's branches, and it rises with temperature too."""
     from paper_2512_13194_amd import inputs
     from paper_2512_13194_amd.sampler import EarsVerifier, acceptance_sweep
-    print("sampler: entropy measure", flush=True)
+    print("sampler: %s measure" % measure, flush=True)
+    ora_measure = {"entropy": oracle.UNC_ENTROPY, "variance": oracle.UNC_VARIANCE}[measure]
     T, beta = 0.9, 0.3
     batch = inputs.make_rect(48, 5, 32000, torch.bfloat16, T=T, data_seed=43, draft_noise=1.0,
                              device="cuda")
-    ver = EarsVerifier(temperature=T, beta=beta, seed=5, telemetry=True, uncertainty="entropy")
+    ver = EarsVerifier(temperature=T, beta=beta, seed=5, telemetry=True, uncertainty=measure)
     res = ver.verify(batch.target, batch.draft, batch.tokens)
     torch.cuda.synchronize()
     ora = oracle.verify(inputs.logits_to_numpy(batch.target), inputs.logits_to_numpy(batch.draft),
                         batch.tokens.cpu().numpy(), float(np.float32(T)), float(np.float32(beta)),
-                        ver.step_seed(0), nthreads=NTHREADS, uncertainty=oracle.UNC_ENTROPY)
+                        ver.step_seed(0), nthreads=NTHREADS, uncertainty=ora_measure)
     assert np.array_equal(res.accept_len.cpu().numpy(), ora.accept_len)
     assert np.array_equal(res.tokens.cpu().numpy(), ora.tokens)
     assert np.array_equal(res.path.cpu().numpy().reshape(ora.path.shape), ora.path)
     assert ver.counts["pardon"] == int((ora.path == 2).sum())
-    rows = acceptance_sweep(batch, [0.0, 0.2, 0.6], T, seed=5, uncertainty="entropy")
+    rows = acceptance_sweep(batch, [0.0, 0.2, 0.6], T, seed=5, uncertainty=measure)
     assert rows[0]["pardon_rate"] == 0.0
     assert rows[0]["mean_accept_len"] <= rows[1]["mean_accept_len"] <= rows[2]["mean_accept_len"]
     means = []
     for temp in (0.5, 1.0, 1.5):
-        r = EarsVerifier(temperature=temp, beta=0.1, seed=1, uncertainty="entropy").verify(
+        r = EarsVerifier(temperature=temp, beta=0.1, seed=1, uncertainty=measure).verify(
             batch.target, batch.draft, batch.tokens, want_stats=True)
         torch.cuda.synchronize()
         means.append(r.stats[:, 6].mean().item())
     assert means[0] < means[1] < means[2]
     with pytest.raises(ValueError):
-        EarsVerifier(uncertainty="variance")
+        EarsVerifier(uncertainty="kurtosis")
