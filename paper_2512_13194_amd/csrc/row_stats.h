@@ -32,23 +32,42 @@ namespace ears {
 //                     variance of the one-hot outcome is 1 - W/S^2: one more FMA per element.
 enum { kMeasureNone = 0, kMeasureEntropy = 1, kMeasureVariance = 2 };
 
+//
+// A chunk's sum joins the running sum through an error-free addition (two-sum): the rounding error
+// of S + chunk goes to a second word S_lo.  Without it a lane whose S is dominated by one term (a
+// sharply peaked row: S ~ 1, every chunk ~ 1e-8..1e-7) rounds each chunk to a multiple of ulp(S)
+// and Z drifts by several 1e-7.
+__device__ __forceinline__ void add_chunk(float& hi, float& lo, float x) {
+  const float t = hi + x;
+  const float bv = t - hi;
+  lo += (hi - (t - bv)) + (x - bv);
+  hi = t;
+}
+
 template <int N, int kMeasure>
 __device__ __forceinline__ void accumulate(const float (&f)[N], float c, float& m_run, float& mc,
-                                           float& S, float& W) {
+                                           float& S, float& S_lo, float& W, float& W_lo) {
   float cm = f[0];
 #pragma unroll
   for (int j = 1; j < N; ++j) cm = fmaxf(cm, f[j]);
   if (cm > m_run) {
     const float mc_new = cm * c;
     if (m_run == -INFINITY) {
-      S = 0.0f;
-      W = 0.0f;
+      S = S_lo = 0.0f;
+      W = W_lo = 0.0f;
     } else {
       const float d = mc - mc_new;
       const float scale = __builtin_amdgcn_exp2f(d);
-      if (kMeasure == kMeasureEntropy) W = scale * fmaf(d, S, W);
-      if (kMeasure == kMeasureVariance) W = (scale * scale) * W;
+      if (kMeasure == kMeasureEntropy) {
+        W = scale * fmaf(d, S, W);
+        W_lo *= scale;
+      }
+      if (kMeasure == kMeasureVariance) {
+        W = (scale * scale) * W;
+        W_lo *= scale * scale;
+      }
       S *= scale;
+      S_lo *= scale;
     }
     m_run = cm;
     mc = mc_new;
@@ -64,8 +83,10 @@ __device__ __forceinline__ void accumulate(const float (&f)[N], float c, float& 
     if (kMeasure == kMeasureEntropy) w[j & 3] = fmaf(e, y, w[j & 3]);
     if (kMeasure == kMeasureVariance) w[j & 3] = fmaf(e, e, w[j & 3]);
   }
-  S += (s[0] + s[1]) + (s[2] + s[3]);
-  if (kMeasure != kMeasureNone) W += (w[0] + w[1]) + (w[2] + w[3]);
+  add_chunk(S, S_lo, (s[0] + s[1]) + (s[2] + s[3]));
+  // the entropy's W has no dominant term (the largest e comes with y ~ 0): a plain sum serves
+  if (kMeasure == kMeasureEntropy) W += (w[0] + w[1]) + (w[2] + w[3]);
+  if (kMeasure == kMeasureVariance) add_chunk(W, W_lo, (w[0] + w[1]) + (w[2] + w[3]));
 }
 
 // Streams one row; on return thread 0 holds the row maximum M, Z = sum exp((l - M)/T) and in
@@ -75,7 +96,7 @@ __device__ __forceinline__ void row_pass(const typename DT::storage* base, int V
                                          float* sh_m, double* sh_s, float& M_out, double& Z_out,
                                          double& H_out) {
   const int tid = (int)threadIdx.x;
-  float m_run = -INFINITY, mc = 0.0f, S = 0.0f, W = 0.0f;
+  float m_run = -INFINITY, mc = 0.0f, S = 0.0f, S_lo = 0.0f, W = 0.0f, W_lo = 0.0f;
 
   // scalar head up to the first 16-byte boundary and scalar tail after the last whole vector
   // (both empty when rows are 16-byte multiples)
@@ -88,7 +109,7 @@ __device__ __forceinline__ void row_pass(const typename DT::storage* base, int V
   const int ntail = V - tail0;
   if (tid < head + ntail) {
     float f[1] = {DT::load(base, tid < head ? tid : tail0 + (tid - head))};
-    accumulate<1, kMeasure>(f, c, m_run, mc, S, W);
+    accumulate<1, kMeasure>(f, c, m_run, mc, S, S_lo, W, W_lo);
   }
 
   const uint4* vp = reinterpret_cast<const uint4*>(base + head);
@@ -107,7 +128,7 @@ __device__ __forceinline__ void row_pass(const typename DT::storage* base, int V
 #pragma unroll
       for (int j = 0; j < kPer; ++j) f[u * kPer + j] = g[j];
     }
-    accumulate<kUnroll * kPer, kMeasure>(f, c, m_run, mc, S, W);
+    accumulate<kUnroll * kPer, kMeasure>(f, c, m_run, mc, S, S_lo, W, W_lo);
   }
 
   // merge the lanes of the workgroup
@@ -121,11 +142,12 @@ __device__ __forceinline__ void row_pass(const typename DT::storage* base, int V
   for (int w = 1; w < kWavesPerBlock; ++w) M = fmaxf(M, sh_m[w]);
   const float Mc = M * c;
   const float scale = (m_run == -INFINITY) ? 0.0f : __builtin_amdgcn_exp2f(mc - Mc);
-  const double part = wave_sum((double)S * (double)scale);
+  const double S2 = (double)S + (double)S_lo, W2 = (double)W + (double)W_lo;
+  const double part = wave_sum(S2 * (double)scale);
   double wpart = 0.0;
   if (kMeasure == kMeasureEntropy)
-    wpart = wave_sum((double)scale * ((double)W + (double)(mc - Mc) * (double)S));
-  if (kMeasure == kMeasureVariance) wpart = wave_sum(((double)scale * (double)scale) * (double)W);
+    wpart = wave_sum((double)scale * (W2 + (double)(mc - Mc) * S2));
+  if (kMeasure == kMeasureVariance) wpart = wave_sum(((double)scale * (double)scale) * W2);
   if (lane == 0) {
     sh_s[wave] = part;
     if (kMeasure != kMeasureNone) sh_s[kWavesPerBlock + wave] = wpart;

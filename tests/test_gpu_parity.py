@@ -227,6 +227,32 @@ def test_residual_support_floor_on_nearly_identical_peaked_rows(ears, oracle):
         assert (ora.accept_len == 0).sum() > B // 2
 
 
+def test_small_terms_beside_a_dominant_one_are_kept(ears, oracle):
+    """A wide row with one entry far above the rest: Z = 1 + 3e-4, made of one term of 1 and 128255
+    terms of ~2e-9.  A lane that adds those to a running sum near 1 in plain fp32 rounds every chunk
+    to a multiple of 1.2e-7 and Z drifts by 5e-7; the chunk sums are added error-free instead."""
+    _log("dominant term plus many small ones")
+    B, K, V, T = 4, 2, 128256, 10.0
+    g = torch.Generator(device="cuda").manual_seed(77)
+    target = torch.randn(B, K + 1, V, generator=g, device="cuda")
+    idx = torch.randint(0, V, (B, K + 1, 1), generator=g, device="cuda")
+    target.scatter_add_(2, idx, torch.full((B, K + 1, 1), 200.0, device="cuda"))
+    draft = (target[:, :K] + 0.5 * torch.randn(B, K, V, generator=g, device="cuda")).contiguous()
+    tokens = torch.randint(0, V, (B, K), generator=g, device="cuda", dtype=torch.int32)
+    from paper_2512_13194_amd import inputs
+    for unc, ounc, bound in ((ears.EARS_UNCERTAINTY_MAXPROB, oracle.UNC_MAXPROB, 2.5e-7),
+                             (ears.EARS_UNCERTAINTY_VARIANCE, oracle.UNC_VARIANCE, 5e-7)):
+        out = ears.ears_verify_ex(target, draft, tokens, temperature=T, beta=1.0, seed=3, uncertainty=unc,
+                                  want_stats=True)
+        torch.cuda.synchronize()
+        ora = oracle.verify(inputs.logits_to_numpy(target), inputs.logits_to_numpy(draft),
+                            tokens.cpu().numpy(), T, 1.0, 3, nthreads=NTHREADS, uncertainty=ounc)
+        st = out["stats"].cpu().numpy()
+        assert np.abs(st[:, 1] / ora.d("Z_t").reshape(-1) - 1.0).max() < 2.5e-7
+        assert 1e-4 < ora.d("unc").max() < 2e-3
+        assert np.abs(st[:, 6] - ora.d("unc").reshape(-1)).max() < bound
+
+
 def test_seq_ids_batch_order_invariance_and_determinism(ears, oracle):
     from paper_2512_13194_amd import inputs
     _log("seq ids / determinism")
