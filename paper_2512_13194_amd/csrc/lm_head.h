@@ -229,30 +229,36 @@ void lm_head_kernel(LmHeadProblem p) {
     }
     // the other half-wave holds the other 64 entries of the same token's 128-slice
     m = fmaxf(m, __shfl_xor(m, 32, 64));
-    float S = 0.0f, W = 0.0f;
+    // 16 short fp32 sums of 4 terms each, combined in fp64: the slice that holds a row's dominant
+    // entry (one term of 1 beside terms near 1e-8) then loses at most three small terms to ulp(1)
+    double S = 0.0, W = 0.0;
     if (m != -INFINITY) {
       const float mc = m * c;
-      float s4[4] = {0.0f, 0.0f, 0.0f, 0.0f};
-      float w4[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+      float s16[16], w16[16];
+#pragma unroll
+      for (int r = 0; r < 16; ++r) s16[r] = w16[r] = 0.0f;
 #pragma unroll
       for (int i = 0; i < 4; ++i)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
           const float y = fmaxf(fmaf(xr[i][r], c, -mc), -126.0f);  // a masked entry adds 0 * finite
           const float e = __builtin_amdgcn_exp2f(y);
-          s4[r & 3] += e;
-          w4[r & 3] = fmaf(e, y, w4[r & 3]);
+          s16[r] += e;
+          w16[r] = fmaf(e, y, w16[r]);
         }
-      S = (s4[0] + s4[1]) + (s4[2] + s4[3]);
-      W = (w4[0] + w4[1]) + (w4[2] + w4[3]);
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        S += (double)s16[r];
+        W += (double)w16[r];
+      }
     }
     S += __shfl_xor(S, 32, 64);
     W += __shfl_xor(W, 32, 64);
     if (half == 0 && tok < p.N) {
       const size_t slot = (size_t)tok * p.nparts + vt * kLmPartsPerTile + wv;
       p.part_m[slot] = m;
-      p.part_S[slot] = S;
-      p.part_W[slot] = W;
+      p.part_S[slot] = (float)S;
+      p.part_W[slot] = (float)W;
     }
   }
   __syncthreads();

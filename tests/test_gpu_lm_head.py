@@ -72,6 +72,27 @@ def test_projection_and_statistics_small(ears, oracle, N, D, V):
     _check_stats(oracle, got, row_max.cpu().numpy(), row_sum.cpu().numpy(), T, range(N))
 
 
+def test_statistics_keep_small_terms_beside_a_dominant_logit(ears, oracle):
+    """Rows whose softmax is dominated by one entry (weight row n is a multiple of hidden row n):
+    Z = 1 + ~4e-4 from thousands of terms near 1e-8.  The slice that holds the dominant entry sums
+    its terms in short fp32 runs combined in fp64, so they are not rounded away at ulp(1)."""
+    _log("lm_head: dominant logit")
+    N, D, V = 64, 128, 8192
+    hidden, weight = _operands(N, D, V, 9)
+    h = hidden.float()
+    weight[:N] = (h * (20.0 / (h * h).sum(1, keepdim=True))).to(torch.bfloat16)
+    logits, rm, rs = ears.ears_lm_head_bf16(hidden, weight, temperature=1.0)
+    torch.cuda.synchronize()
+    bits, rs = _bits(logits), rs.cpu().numpy()
+    worst = 0.0
+    for n in range(N):
+        _, m, Z, _ = oracle.softmax(bits[n], 1.0)
+        assert 1.0 < Z < 1.01
+        worst = max(worst, abs(rs[n] / Z - 1.0))
+    _log("  worst relative error of Z: %.2e" % worst)
+    assert worst < 2e-7
+
+
 def test_per_row_temperature(ears, oracle):
     _log("lm_head per-row temperature")
     N, D, V = 40, 128, 3000
