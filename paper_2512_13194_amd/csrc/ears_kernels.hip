@@ -185,7 +185,7 @@ const char* ears_status_string(int status) {
     case EARS_OK: return "ok";
     case EARS_ERR_NULL: return "a required pointer is NULL";
     case EARS_ERR_SHAPE: return "B, K, V or total_draft_rows out of range";
-    case EARS_ERR_PARAM: return "temperature, beta or stages invalid";
+    case EARS_ERR_PARAM: return "temperature, beta, stages or uncertainty measure invalid";
     case EARS_ERR_ALIGN: return "a pointer is not aligned as documented";
     case EARS_ERR_DTYPE: return "unknown dtype";
     case EARS_ERR_WORKSPACE: return "workspace missing or too small";
