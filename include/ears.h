@@ -155,7 +155,9 @@ size_t ears_workspace_bytes(int64_t total_draft_rows, int B, int V);
  *   temperature_per_seq, beta_per_seq   device [B] or NULL; when NULL the scalar is used
  *   uncertainty      an ears_uncertainty; the simple entry points use EARS_UNCERTAINTY_MAXPROB.
  *                    The statistics stage caches what the selected measure needs, so STATS and
- *                    DECIDE must be called with the same value
+ *                    DECIDE are called with the same value; a DECIDE stage that asks for a
+ *                    measure the cached statistics do not carry decides with MAXPROB instead
+ *                    and raises bit 1 of the status word
  *   seq_ids          device [B] int64 or NULL: RNG id of each sequence (low 56 bits used);
  *                    NULL means 0..B-1.  With explicit ids a sequence's result does not depend
  *                    on its slot in the batch.
@@ -169,6 +171,8 @@ size_t ears_workspace_bytes(int64_t total_draft_rows, int B, int V);
  *                    tolerance (the three branches of Section 3.2 step 5)
  *   status_word      optional device uint32; bits are OR-ed in, never cleared:
  *                    bit 0 = some draft token was outside [0, V)
+ *                    bit 1 = a separate DECIDE stage asked for an uncertainty measure other
+ *                            than the one cached by STATS or ears_import_stats
  * ------------------------------------------------------------------------------------------- */
 int ears_verify_ex(int dtype, const void* target_logits, const void* draft_logits,
                    const int32_t* draft_tokens, const int64_t* row_offsets,
@@ -242,7 +246,7 @@ int ears_row_stats(int dtype, const void* logits, int64_t rows, int V, float tem
  *   target_row_entropy                   same shape, or NULL; required before a DECIDE stage
  *                                        with EARS_UNCERTAINTY_ENTROPY (the VARIANCE measure is
  *                                        not carried by imported statistics: it needs the STATS
- *                                        stage of ears_verify_ex)
+ *                                        stage of ears_verify_ex; see bit 1 of its status word)
  *   draft_row_max / draft_row_sumexp     [total_draft_rows]
  * Other arguments as for ears_verify_ex. */
 int ears_import_stats(int dtype, const void* target_logits, const void* draft_logits,

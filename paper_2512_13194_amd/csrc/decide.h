@@ -80,7 +80,11 @@ __device__ __forceinline__ int first_reject_scan(const Problem& p, int b, int la
         decision = p.decisions[r];
       } else {
         const double Zt = p.Z[2 * r];
-        const double unc = p.unc_mode ? p.unc[r] : 1.0 - 1.0 / Zt;  // max P_t = 1/Z_t
+        // The cached statistics carry one alternative measure at most; asked for another, the
+        // decision falls back to 1 - max P_t = 1 - 1/Z_t and says so in the status word.
+        const bool cached = p.unc_mode != 0 && *p.unc_tag == (uint32_t)p.unc_mode;
+        if (p.unc_mode != 0 && !cached && i == 0 && p.status_word) atomicOr(p.status_word, 2u);
+        const double unc = cached ? p.unc[r] : 1.0 - 1.0 / Zt;
         const double U = accept_uniform(p.seed, seq_rng_id(p, b), (uint32_t)i);
         decision = decide_position(p, b, r, p.tokens[r], U, (double)p.m[2 * r], Zt,
                                    (double)p.lx[2 * r], (double)p.m[2 * r + 1], p.Z[2 * r + 1],

@@ -45,8 +45,9 @@ struct Problem {
   double* Z;
   float* m;
   float* lx;
-  double* unc;          // [R] entropy-based uncertainty H(p_t)/log V (only when unc_mode == 1)
-  int unc_mode;         // 0: 1 - max p_t, 1: normalised entropy
+  double* unc;          // [R] uncertainty of the alternative measures (when unc_mode != 0)
+  uint32_t* unc_tag;    // [1] which measure unc[] holds: written by whoever fills the statistics
+  int unc_mode;         // 0: 1 - max p_t, 1: normalised entropy, 2: total variance
   int32_t* decisions;   // [R] per position: 0 reject, 1 primary accept, 2 accepted by tolerance
   // sampling stage scratch: per-chunk records
   uint32_t* records;    // [B, S, kRecordWords]

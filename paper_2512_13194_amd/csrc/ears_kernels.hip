@@ -41,7 +41,7 @@ namespace ears {
 // Host side.
 // =================================================================================================
 struct WorkspaceLayout {
-  size_t off_Z, off_m, off_lx, off_unc, off_decisions, off_records, total;
+  size_t off_Z, off_m, off_lx, off_unc, off_unc_tag, off_decisions, off_records, total;
   int S, chunk;  // how the sampling stage splits a row
 };
 
@@ -73,6 +73,7 @@ static bool workspace_layout(int64_t R, int B, int V, WorkspaceLayout* w) {
   w->off_m = o;        o = align_up(o + (size_t)(2 * R) * sizeof(float), 256);
   w->off_lx = o;       o = align_up(o + (size_t)(2 * R) * sizeof(float), 256);
   w->off_unc = o;      o = align_up(o + (size_t)R * sizeof(double), 256);
+  w->off_unc_tag = o;  o = align_up(o + sizeof(uint32_t), 256);
   w->off_decisions = o; o = align_up(o + (size_t)R * sizeof(int32_t), 256);
   w->off_records = o;  o = align_up(o + (size_t)B * S4 * kRecordWords * sizeof(uint32_t), 256);
   w->total = o;
@@ -236,6 +237,7 @@ int ears_verify_ex(int dtype, const void* target_logits, const void* draft_logit
   p.m = reinterpret_cast<float*>(ws + lay.off_m);
   p.lx = reinterpret_cast<float*>(ws + lay.off_lx);
   p.unc = reinterpret_cast<double*>(ws + lay.off_unc);
+  p.unc_tag = reinterpret_cast<uint32_t*>(ws + lay.off_unc_tag);
   p.unc_mode = uncertainty;
   p.decisions = reinterpret_cast<int32_t*>(ws + lay.off_decisions);
   p.records = reinterpret_cast<uint32_t*>(ws + lay.off_records);
@@ -494,6 +496,7 @@ int ears_import_stats(int dtype, const void* target_logits, const void* draft_lo
   p.m = reinterpret_cast<float*>(ws + lay.off_m);
   p.lx = reinterpret_cast<float*>(ws + lay.off_lx);
   p.unc = reinterpret_cast<double*>(ws + lay.off_unc);
+  p.unc_tag = reinterpret_cast<uint32_t*>(ws + lay.off_unc_tag);
   hipStream_t s = static_cast<hipStream_t>(stream);
   const dim3 grid((unsigned)((total_draft_rows + kBlock - 1) / kBlock));
   if (dtype == EARS_F32)

@@ -346,6 +346,7 @@ __global__ __launch_bounds__(kBlock) void import_stats_kernel(Problem p, const f
   // entropy-based uncertainty H / log V of the target row (Section 5), when the producer has it
   if (t_entropy)
     p.unc[r] = p.V > 1 ? fmin(fmax(t_entropy[r + b] / log((double)p.V), 0.0), 1.0) : 0.0;
+  if (r == 0) *p.unc_tag = t_entropy ? 1u : 0u;  // as the statistics pass tags its measure
 }
 
 }  // namespace ears

@@ -217,6 +217,7 @@ __global__ __launch_bounds__(kBlock) void row_stats_kernel(Problem p) {
     if (kMeasure == kMeasureEntropy) unc = V > 1 ? fmin(fmax(Ht / log((double)V), 0.0), 1.0) : 0.0;
     if (kMeasure == kMeasureVariance) unc = fmin(fmax(Ht, 0.0), 1.0);
     if (kMeasure != kMeasureNone) p.unc[r] = unc;
+    if (r == 0) *p.unc_tag = (uint32_t)kMeasure;
     if (kDecide)
       p.decisions[r] = decide_position(p, b, r, x, U, (double)Mt, Zt, (double)lxt, (double)Md, Zd,
                                        (double)lxd, unc);

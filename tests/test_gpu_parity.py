@@ -373,6 +373,36 @@ def test_alternative_uncertainty_masked_peaked_ragged_and_stages(ears, oracle, m
     assert torch.equal(b["accept_len"], out["accept_len"]) and torch.equal(b["tokens"], out["tokens"])
 
 
+def test_decide_stage_with_a_measure_the_cache_does_not_hold(ears, oracle):
+    """STATS caches one alternative measure.  A later DECIDE that asks for another one decides with
+    1 - max P_t (always available from Z) and raises bit 1 of the status word; a matching one does
+    not."""
+    from paper_2512_13194_amd import inputs
+    _log("measure mismatch between stages")
+    batch = inputs.make_rect(24, 4, 3000, torch.bfloat16, T=1.0, data_seed=91, draft_noise=1.0,
+                             device="cuda")
+    kw = dict(temperature=1.0, beta=0.8, seed=4)
+    later = ears.EARS_STAGE_DECIDE | ears.EARS_STAGE_SAMPLE
+    a = ears.ears_verify_ex(batch.target, batch.draft, batch.tokens, stages=ears.EARS_STAGE_STATS,
+                            uncertainty=ears.EARS_UNCERTAINTY_ENTROPY, **kw)
+    status = torch.zeros(1, dtype=torch.int32, device="cuda")
+    ok = ears.ears_verify_ex(batch.target, batch.draft, batch.tokens, stages=later, workspace=a["workspace"],
+                             uncertainty=ears.EARS_UNCERTAINTY_ENTROPY, status_word=status, **kw)
+    torch.cuda.synchronize()
+    assert int(status.item()) == 0
+    other = ears.ears_verify_ex(batch.target, batch.draft, batch.tokens, stages=later, workspace=a["workspace"],
+                                uncertainty=ears.EARS_UNCERTAINTY_VARIANCE, status_word=status, **kw)
+    torch.cuda.synchronize()
+    assert int(status.item()) == 2
+    plain = ears.ears_verify_ex(batch.target, batch.draft, batch.tokens, **kw)
+    whole = ears.ears_verify_ex(batch.target, batch.draft, batch.tokens,
+                                uncertainty=ears.EARS_UNCERTAINTY_ENTROPY, **kw)
+    torch.cuda.synchronize()
+    assert torch.equal(other["accept_len"], plain["accept_len"]) and torch.equal(other["tokens"], plain["tokens"])
+    assert torch.equal(ok["accept_len"], whole["accept_len"]) and torch.equal(ok["tokens"], whole["tokens"])
+    assert not torch.equal(plain["accept_len"], whole["accept_len"])   # the measures do differ here
+
+
 def test_ragged_small(ears, oracle):
     from paper_2512_13194_amd import inputs
     _log("ragged small")
