@@ -30,7 +30,9 @@
  *    return without synchronising; outputs are valid once the caller has synchronised `stream`.
  *  - Return value: an ears_status.  All argument checks happen on the host before any HIP call.
  *  - Logits: finite values and -inf (a masked vocabulary entry, probability 0) are supported as
- *    long as every row has a finite entry; NaN and +inf are undefined behaviour.
+ *    long as every row has a finite entry.  A NaN or +inf logit, or a row without a finite entry,
+ *    makes the results of its sequence undefined (every emitted token is still an index in
+ *    [0, V) or -1, other sequences are not affected) and sets bit 2 of the status word.
  *  - A draft token outside [0, V) is rejected at its position and sets bit 0 of the optional
  *    device status word.
  *  - Two calls that share a workspace (or the library-owned scratch of the simple entry points)
@@ -173,6 +175,10 @@ size_t ears_workspace_bytes(int64_t total_draft_rows, int B, int V);
  *                    bit 0 = some draft token was outside [0, V)
  *                    bit 1 = a separate DECIDE stage asked for an uncertainty measure other
  *                            than the one cached by STATS or ears_import_stats
+ *                    bit 2 = the STATS stage met a row whose sum of exponentials is not a
+ *                            positive finite number (a NaN or +inf logit, or no finite entry at
+ *                            all): the results of that sequence are undefined, the others' are
+ *                            not affected
  * ------------------------------------------------------------------------------------------- */
 int ears_verify_ex(int dtype, const void* target_logits, const void* draft_logits,
                    const int32_t* draft_tokens, const int64_t* row_offsets,

@@ -218,6 +218,9 @@ __global__ __launch_bounds__(kBlock) void row_stats_kernel(Problem p) {
     if (kMeasure == kMeasureVariance) unc = fmin(fmax(Ht, 0.0), 1.0);
     if (kMeasure != kMeasureNone) p.unc[r] = unc;
     if (r == 0) *p.unc_tag = (uint32_t)kMeasure;
+    // a NaN or +inf logit, or a row without any finite entry, leaves Z outside (0, inf)
+    if (p.status_word && !(Zt > 0.0 && Zt < INFINITY && Zd > 0.0 && Zd < INFINITY))
+      atomicOr(p.status_word, 4u);
     if (kDecide)
       p.decisions[r] = decide_position(p, b, r, x, U, (double)Mt, Zt, (double)lxt, (double)Md, Zd,
                                        (double)lxd, unc);

@@ -403,6 +403,38 @@ def test_decide_stage_with_a_measure_the_cache_does_not_hold(ears, oracle):
     assert not torch.equal(plain["accept_len"], whole["accept_len"])   # the measures do differ here
 
 
+def test_non_finite_logits_are_flagged_and_stay_contained(ears, oracle):
+    """A NaN, a +inf, and a fully masked row in three sequences: the call completes, status bit 2 is
+    raised, every emitted token of those sequences is a valid index or -1, and all other sequences
+    match the oracle exactly."""
+    from paper_2512_13194_amd import inputs
+    _log("non-finite logits")
+    B, K, V, T = 12, 3, 5000, 1.0
+    batch = inputs.make_rect(B, K, V, torch.float32, T=T, data_seed=92, draft_noise=1.0, device="cuda")
+    clean_t, clean_d = batch.target.clone(), batch.draft.clone()
+    batch.target[2, 1, 77] = float("nan")
+    batch.draft[5, 0, 4000] = float("inf")
+    batch.target[9, 2, :] = float("-inf")
+    status = torch.zeros(1, dtype=torch.int32, device="cuda")
+    out = ears.ears_verify_ex(batch.target, batch.draft, batch.tokens, temperature=T, beta=0.3, seed=8,
+                              status_word=status)
+    torch.cuda.synchronize()
+    assert int(status.item()) & 4 == 4
+    tok = out["tokens"].view(B, K + 1).cpu().numpy()
+    acc = out["accept_len"].cpu().numpy()
+    assert ((tok >= -1) & (tok < V)).all() and ((acc >= 0) & (acc <= K)).all()
+    ora = oracle.verify(inputs.logits_to_numpy(clean_t), inputs.logits_to_numpy(clean_d),
+                        batch.tokens.cpu().numpy(), T, float(np.float32(0.3)), 8, nthreads=NTHREADS)
+    good = np.array([b for b in range(B) if b not in (2, 5, 9)])
+    assert np.array_equal(acc[good], ora.accept_len[good])
+    assert np.array_equal(tok[good], ora.tokens[good])
+    # finite inputs leave the bit clear
+    status.zero_()
+    ears.ears_verify_ex(clean_t, clean_d, batch.tokens, temperature=T, beta=0.3, seed=8, status_word=status)
+    torch.cuda.synchronize()
+    assert int(status.item()) == 0
+
+
 def test_ragged_small(ears, oracle):
     from paper_2512_13194_amd import inputs
     _log("ragged small")
