@@ -33,41 +33,27 @@ namespace ears {
 enum { kMeasureNone = 0, kMeasureEntropy = 1, kMeasureVariance = 2 };
 
 //
-// A chunk's sum joins the running sum through an error-free addition (two-sum): the rounding error
-// of S + chunk goes to a second word S_lo.  Without it a lane whose S is dominated by one term (a
-// sharply peaked row: S ~ 1, every chunk ~ 1e-8..1e-7) rounds each chunk to a multiple of ulp(S)
-// and Z drifts by several 1e-7.
-__device__ __forceinline__ void add_chunk(float& hi, float& lo, float x) {
-  const float t = hi + x;
-  const float bv = t - hi;
-  lo += (hi - (t - bv)) + (x - bv);
-  hi = t;
-}
-
+// A chunk is summed in fp32; the chunk sums are added to the lane's running sums in fp64 (one
+// conversion and one full-rate fp64 add per chunk).  With an fp32 running sum, a lane whose S is
+// dominated by one term (a sharply peaked row: S ~ 1, every chunk ~ 1e-8..1e-7) rounds each chunk
+// to a multiple of ulp(S) and Z drifts by several 1e-7.
 template <int N, int kMeasure>
 __device__ __forceinline__ void accumulate(const float (&f)[N], float c, float& m_run, float& mc,
-                                           float& S, float& S_lo, float& W, float& W_lo) {
+                                           double& S, double& W) {
   float cm = f[0];
 #pragma unroll
   for (int j = 1; j < N; ++j) cm = fmaxf(cm, f[j]);
   if (cm > m_run) {
     const float mc_new = cm * c;
     if (m_run == -INFINITY) {
-      S = S_lo = 0.0f;
-      W = W_lo = 0.0f;
+      S = 0.0;
+      W = 0.0;
     } else {
       const float d = mc - mc_new;
-      const float scale = __builtin_amdgcn_exp2f(d);
-      if (kMeasure == kMeasureEntropy) {
-        W = scale * fmaf(d, S, W);
-        W_lo *= scale;
-      }
-      if (kMeasure == kMeasureVariance) {
-        W = (scale * scale) * W;
-        W_lo *= scale * scale;
-      }
+      const double scale = (double)__builtin_amdgcn_exp2f(d);
+      if (kMeasure == kMeasureEntropy) W = scale * ((double)d * S + W);
+      if (kMeasure == kMeasureVariance) W = (scale * scale) * W;
       S *= scale;
-      S_lo *= scale;
     }
     m_run = cm;
     mc = mc_new;
@@ -83,10 +69,8 @@ __device__ __forceinline__ void accumulate(const float (&f)[N], float c, float& 
     if (kMeasure == kMeasureEntropy) w[j & 3] = fmaf(e, y, w[j & 3]);
     if (kMeasure == kMeasureVariance) w[j & 3] = fmaf(e, e, w[j & 3]);
   }
-  add_chunk(S, S_lo, (s[0] + s[1]) + (s[2] + s[3]));
-  // the entropy's W has no dominant term (the largest e comes with y ~ 0): a plain sum serves
-  if (kMeasure == kMeasureEntropy) W += (w[0] + w[1]) + (w[2] + w[3]);
-  if (kMeasure == kMeasureVariance) add_chunk(W, W_lo, (w[0] + w[1]) + (w[2] + w[3]));
+  S += (double)((s[0] + s[1]) + (s[2] + s[3]));
+  if (kMeasure != kMeasureNone) W += (double)((w[0] + w[1]) + (w[2] + w[3]));
 }
 
 // Streams one row; on return thread 0 holds the row maximum M, Z = sum exp((l - M)/T) and in
@@ -96,7 +80,8 @@ __device__ __forceinline__ void row_pass(const typename DT::storage* base, int V
                                          float* sh_m, double* sh_s, float& M_out, double& Z_out,
                                          double& H_out) {
   const int tid = (int)threadIdx.x;
-  float m_run = -INFINITY, mc = 0.0f, S = 0.0f, S_lo = 0.0f, W = 0.0f, W_lo = 0.0f;
+  float m_run = -INFINITY, mc = 0.0f;
+  double S = 0.0, W = 0.0;
 
   // scalar head up to the first 16-byte boundary and scalar tail after the last whole vector
   // (both empty when rows are 16-byte multiples)
@@ -109,7 +94,7 @@ __device__ __forceinline__ void row_pass(const typename DT::storage* base, int V
   const int ntail = V - tail0;
   if (tid < head + ntail) {
     float f[1] = {DT::load(base, tid < head ? tid : tail0 + (tid - head))};
-    accumulate<1, kMeasure>(f, c, m_run, mc, S, S_lo, W, W_lo);
+    accumulate<1, kMeasure>(f, c, m_run, mc, S, W);
   }
 
   const uint4* vp = reinterpret_cast<const uint4*>(base + head);
@@ -128,7 +113,7 @@ __device__ __forceinline__ void row_pass(const typename DT::storage* base, int V
 #pragma unroll
       for (int j = 0; j < kPer; ++j) f[u * kPer + j] = g[j];
     }
-    accumulate<kUnroll * kPer, kMeasure>(f, c, m_run, mc, S, S_lo, W, W_lo);
+    accumulate<kUnroll * kPer, kMeasure>(f, c, m_run, mc, S, W);
   }
 
   // merge the lanes of the workgroup
@@ -142,12 +127,11 @@ __device__ __forceinline__ void row_pass(const typename DT::storage* base, int V
   for (int w = 1; w < kWavesPerBlock; ++w) M = fmaxf(M, sh_m[w]);
   const float Mc = M * c;
   const float scale = (m_run == -INFINITY) ? 0.0f : __builtin_amdgcn_exp2f(mc - Mc);
-  const double S2 = (double)S + (double)S_lo, W2 = (double)W + (double)W_lo;
-  const double part = wave_sum(S2 * (double)scale);
+  const double part = wave_sum(S * (double)scale);
   double wpart = 0.0;
   if (kMeasure == kMeasureEntropy)
-    wpart = wave_sum((double)scale * (W2 + (double)(mc - Mc) * S2));
-  if (kMeasure == kMeasureVariance) wpart = wave_sum(((double)scale * (double)scale) * W2);
+    wpart = wave_sum((double)scale * (W + (double)(mc - Mc) * S));
+  if (kMeasure == kMeasureVariance) wpart = wave_sum(((double)scale * (double)scale) * W);
   if (lane == 0) {
     sh_s[wave] = part;
     if (kMeasure != kMeasureNone) sh_s[kWavesPerBlock + wave] = wpart;
