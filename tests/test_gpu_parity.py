@@ -230,7 +230,7 @@ def test_residual_support_floor_on_nearly_identical_peaked_rows(ears, oracle):
 def test_small_terms_beside_a_dominant_one_are_kept(ears, oracle):
     """A wide row with one entry far above the rest: Z = 1 + 3e-4, made of one term of 1 and 128255
     terms of ~2e-9.  A lane that adds those to a running sum near 1 in plain fp32 rounds every chunk
-    to a multiple of 1.2e-7 and Z drifts by 5e-7; the chunk sums are added error-free instead."""
+    to a multiple of 1.2e-7 and Z drifts by 5e-7; the chunk sums are added in fp64 instead."""
     _log("dominant term plus many small ones")
     B, K, V, T = 4, 2, 128256, 10.0
     g = torch.Generator(device="cuda").manual_seed(77)
