@@ -224,7 +224,7 @@ int ears_verify_greedy(int dtype, const void* target_logits, const int32_t* draf
  *   out_row_entropy  [N] double or NULL: Shannon entropy (nats) of softmax(logits[n,:] / T), for
  *                    the entropy-based uncertainty measure
  *   workspace        device, 256-byte aligned, >= ears_lm_head_workspace_bytes(N, V) bytes
- * N * V must be below 2^31.
+ * D must not exceed 2^20; the matrices themselves may be larger than 4 GiB.
  * ------------------------------------------------------------------------------------------- */
 size_t ears_lm_head_workspace_bytes(int N, int V);
 

@@ -392,10 +392,8 @@ int ears_lm_head_bf16(const void* hidden, const void* weight, int N, int D, int 
                       void* workspace, size_t workspace_bytes, void* stream) {
   if (!hidden || !weight || !out_logits || !out_row_max || !out_row_sumexp) return EARS_ERR_NULL;
   if (N < 1 || V < 1 || D < kLmBK || D % kLmBK != 0) return EARS_ERR_SHAPE;
-  if ((int64_t)N * (int64_t)V > (int64_t)0x7FFFFFFF) return EARS_ERR_SHAPE;
-  // the kernel addresses both operands with 32-bit byte offsets
-  if ((int64_t)V * D * 2 > (int64_t)0xFFFFFFFF || (int64_t)N * D * 2 > (int64_t)0xFFFFFFFF)
-    return EARS_ERR_SHAPE;
+  // the kernel addresses the 256 rows of a tile with 32-bit byte offsets
+  if (D > (1 << 20)) return EARS_ERR_SHAPE;
   if (!row_temperature && !(std::isfinite(temperature) && temperature > 0.0f)) return EARS_ERR_PARAM;
   if (!aligned(hidden, 16) || !aligned(weight, 16) || !aligned(out_logits, 2) ||
       !aligned(out_row_max, 4) || !aligned(out_row_sumexp, 8) || !aligned(out_row_entropy, 8) ||

@@ -139,13 +139,19 @@ void lm_head_kernel(LmHeadProblem p) {
   const uint32_t ld_chunk_off = (uint32_t)(((lane & 7) ^ lm_swizzle(ld_row)) * 16);
   const uint32_t row_bytes = (uint32_t)(p.D * 2);
   const uint32_t block_stride = 64u * row_bytes;
-  const uint32_t offA = (uint32_t)(v0 + ld_row) * row_bytes + ld_chunk_off;
-  const uint32_t offB = (uint32_t)(n0 + ld_row) * row_bytes + ld_chunk_off;
-  // raw buffer descriptors (stride 0, 32-bit data format): sizes are checked on the host to fit 32 bits
+  const uint32_t offA = (uint32_t)ld_row * row_bytes + ld_chunk_off;
+  const uint32_t offB = offA;
+  // Raw buffer descriptors (stride 0, 32-bit data format) over this tile's rows only: the base is
+  // the tile's first row (64-bit), the extent its rows that exist, so the 32-bit offsets never see
+  // the size of the whole matrix and rows past its end read as zero.
+  const int rows_a = p.V - v0 < kLmTile ? p.V - v0 : kLmTile;
+  const int rows_b = p.N - n0 < kLmTile ? p.N - n0 : kLmTile;
   const __amdgpu_buffer_rsrc_t rA = __builtin_amdgcn_make_buffer_rsrc(
-      const_cast<uint16_t*>(p.weight), 0, (int)((uint32_t)p.V * row_bytes), 0x00020000);
+      const_cast<uint16_t*>(p.weight) + (size_t)v0 * (size_t)p.D, 0, (int)((uint32_t)rows_a * row_bytes),
+      0x00020000);
   const __amdgpu_buffer_rsrc_t rB = __builtin_amdgcn_make_buffer_rsrc(
-      const_cast<uint16_t*>(p.hidden), 0, (int)((uint32_t)p.N * row_bytes), 0x00020000);
+      const_cast<uint16_t*>(p.hidden) + (size_t)n0 * (size_t)p.D, 0, (int)((uint32_t)rows_b * row_bytes),
+      0x00020000);
 
   // ---- fragment reads: lane supplies row (lane & 31), k-offset 8 * (lane >> 5) of each block ----
   const int fr_swz = lm_swizzle(lane & 31);

@@ -182,8 +182,7 @@ def test_lm_head_argument_errors(L):
     assert _lm(L, V=0) == b.EARS_ERR_SHAPE
     assert _lm(L, D=96) == b.EARS_ERR_SHAPE               # D must be a multiple of 64
     assert _lm(L, D=0) == b.EARS_ERR_SHAPE
-    assert _lm(L, N=1 << 16, V=1 << 16) == b.EARS_ERR_SHAPE  # N * V >= 2^31
-    assert _lm(L, V=1 << 20, D=4096) == b.EARS_ERR_SHAPE      # weight beyond 32-bit byte offsets
+    assert _lm(L, D=(1 << 20) + 64) == b.EARS_ERR_SHAPE    # a tile's rows beyond 32-bit byte offsets
     assert _lm(L, T=0.0) == b.EARS_ERR_PARAM
     assert _lm(L, T=float("nan")) == b.EARS_ERR_PARAM
     assert _lm(L, hidden=P + 8) == b.EARS_ERR_ALIGN

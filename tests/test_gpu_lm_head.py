@@ -161,6 +161,38 @@ def test_headline_shape_sampled(ears, oracle):
         assert rm[n] == m and abs(rs[n] - Z) <= 1e-5 * Z
 
 
+def test_weight_matrix_larger_than_4_gib(ears, oracle):
+    """D = 16384, V = 131072 + 700: the weight matrix is 4.3 GB, so its last 700 rows lie beyond
+    what a 32-bit byte offset from the matrix base reaches; every tile addresses its rows from its
+    own base.  Sampled logits (many of them in those rows) against single fp64 dot products, and
+    sampled rows' statistics against the oracle's softmax of the emitted row."""
+    _log("lm_head weight > 4 GiB")
+    N, D, V, T = 300, 16384, 131072 + 700, 1.0
+    g = torch.Generator(device="cuda").manual_seed(17)
+    hidden = torch.randn(N, D, generator=g, device="cuda").to(torch.bfloat16)
+    weight = torch.empty(V, D, dtype=torch.bfloat16, device="cuda")
+    for r0 in range(0, V, 16384):          # generated in slices: no fp32 copy of the whole matrix
+        r1 = min(V, r0 + 16384)
+        weight[r0:r1] = (torch.randn(r1 - r0, D, generator=g, device="cuda") * (2.5 / D ** 0.5)).to(torch.bfloat16)
+    logits, row_max, row_sum = ears.ears_lm_head_bf16(hidden, weight, temperature=T)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(5)
+    ns = np.concatenate([rng.integers(0, N, 400), [0, N - 1, 255, 256]])
+    vs = np.concatenate([rng.integers(0, V, 200), rng.integers(131072, V, 200), [0, 131071, 131072, V - 1]])
+    hb = _bits(hidden)
+    wb = _bits(weight[torch.as_tensor(vs, device="cuda")])          # only the sampled weight rows
+    got = _val(_bits(logits[torch.as_tensor(ns, device="cuda"), torch.as_tensor(vs, device="cuda")]))
+    exact = np.array([oracle.lm_head_dot(hb, wb, int(n), i) for i, n in enumerate(ns)])
+    step = np.maximum(np.abs(exact), 2.0 ** -126) * 2.0 ** -7
+    assert (np.abs(got - exact) <= 0.51 * step + 1e-4).all()
+    rows = [0, 255, 256, N - 1]
+    lb = _bits(logits[torch.as_tensor(rows, device="cuda")])
+    rm, rs = row_max.cpu().numpy(), row_sum.cpu().numpy()
+    for i, n in enumerate(rows):
+        _, m, Z, _ = oracle.softmax(lb[i], T)
+        assert rm[n] == m and abs(rs[n] - Z) <= 1e-5 * Z
+
+
 @pytest.mark.parametrize("dtype,V", [(torch.bfloat16, 32000), (torch.float32, 4099), (torch.bfloat16, 13)])
 def test_precomputed_row_statistics_feed_the_verification(ears, oracle, dtype, V):
     """ears_row_stats on the draft and the target logits separately (as a pipeline would run it
