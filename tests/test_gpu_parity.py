@@ -435,6 +435,20 @@ def test_non_finite_logits_are_flagged_and_stay_contained(ears, oracle):
     assert int(status.item()) == 0
 
 
+def test_logit_buffers_larger_than_4_gib(ears, oracle):
+    """B = 2500, K = 8, V = 128256, bf16: 5.8 GB of target and 5.1 GB of draft logits (20000
+    positions, ten times the headline batch), every output against the oracle."""
+    from paper_2512_13194_amd import inputs
+    _log("logit buffers > 4 GiB")
+    batch = inputs.make_rect(2500, 8, 128256, torch.bfloat16, T=1.0, data_seed=93, draft_noise=0.7,
+                             device="cuda")
+    assert batch.target.numel() * 2 > 2 ** 32 and batch.draft.numel() * 2 > 2 ** 32
+    rep, ora, _ = run_rect(ears, oracle, batch, 1.0, 0.25, 19, check_simple=False)
+    _log("  " + rep.line() + " mean_accept=%.3f" % ora.accept_len.mean())
+    assert rep.exempt_decisions <= 1 and rep.exempt_tokens <= 1
+    assert 0 < (ora.accept_len == 8).sum() < 2500
+
+
 def test_ragged_small(ears, oracle):
     from paper_2512_13194_amd import inputs
     _log("ragged small")
