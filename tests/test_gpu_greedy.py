@@ -54,6 +54,22 @@ def test_greedy_shapes(ears, oracle, B, K, V, dtype):
         assert 0 < acc.sum() < B * K      # both outcomes occur
 
 
+def test_greedy_target_buffer_larger_than_4_gib(ears, oracle):
+    """B = 2500, K = 8, V = 128256, bf16: 5.8 GB of target logits (22500 rows)."""
+    from paper_2512_13194_amd import inputs
+    _log("greedy target buffer > 4 GiB")
+    g = torch.Generator(device="cuda").manual_seed(94)
+    B, K, V = 2500, 8, 128256
+    target = torch.empty(B, K + 1, V, dtype=torch.bfloat16, device="cuda")
+    for b0 in range(0, B, 250):   # generated in slices: no fp32 copy of the whole buffer
+        target[b0:b0 + 250] = (torch.randn(250, K + 1, V, generator=g, device="cuda") * 2.0).to(torch.bfloat16)
+    assert target.numel() * 2 > 2 ** 32
+    tokens = torch.randint(0, V, (B, K), generator=g, device="cuda", dtype=torch.int32)
+    tokens = _plant_prefixes(target, tokens, g)
+    acc = _check_rect(ears, oracle, target, tokens)
+    assert 0 < acc.sum() < B * K
+
+
 def test_greedy_ties_masked_rows_and_bad_tokens(ears, oracle):
     _log("greedy ties / masked")
     V, B, K = 5000, 6, 3
