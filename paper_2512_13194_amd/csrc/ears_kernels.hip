@@ -5,9 +5,10 @@
 //   stage DECIDE : decide_kernel      - ratio, uniform, tolerance, threshold, three-way decision,
 //                                       first-rejection scan (Section 3.2 steps 2-5, Section 3.1)
 //   stage SAMPLE : sample_kernel      - residual / bonus token by Gumbel-max at slot n: a filter that
-//                  select_kernel        leaves a few survivors per row, then the exact choice; when
-//                                       DECIDE and SAMPLE run in one call the scan runs in the
-//                                       filter's prologue
+//                  select_kernel        leaves a few survivors per row, then the exact choice (one
+//                  sample_select_kernel launch for both when a row is split into at most two
+//                                       chunks); when DECIDE and SAMPLE run in one call the scan
+//                                       runs in the filter's prologue
 //
 // The path is bound by HBM bandwidth (every needed row is read once, plus one re-read of the row
 // pair the sampler needs): no matrix-core work in it.
@@ -143,9 +144,18 @@ static int launch(Problem p, int stages, hipStream_t stream) {
                        dim3(kBlock), 0, stream, p);
   }
   if (sample) {
-    hipLaunchKernelGGL((sample_kernel<DT>), dim3((unsigned)p.S, (unsigned)p.B), dim3(kBlock), 0,
-                       stream, p);
-    hipLaunchKernelGGL((select_kernel<DT>), dim3((unsigned)p.B), dim3(kBlock), 0, stream, p);
+    // rows split into one or two chunks: filter and exact choice in one launch
+    if (p.S == 1) {
+      hipLaunchKernelGGL((sample_select_kernel<DT, 1>), dim3(1u, (unsigned)p.B), dim3(kBlock), 0,
+                         stream, p);
+    } else if (p.S == 2) {
+      hipLaunchKernelGGL((sample_select_kernel<DT, 2>), dim3(1u, (unsigned)p.B), dim3(2 * kBlock), 0,
+                         stream, p);
+    } else {
+      hipLaunchKernelGGL((sample_kernel<DT>), dim3((unsigned)p.S, (unsigned)p.B), dim3(kBlock), 0,
+                         stream, p);
+      hipLaunchKernelGGL((select_kernel<DT>), dim3((unsigned)p.B), dim3(kBlock), 0, stream, p);
+    }
   }
   return hipGetLastError() == hipSuccess ? EARS_OK : EARS_ERR_HIP;
 }

@@ -25,7 +25,8 @@
 // Rows the bounds cannot separate (nearly identical target and draft rows, an empty residual,
 // a survivor list that overflows) fall back to an fp64 scan, so the result is always the
 // definition's.  The accept / first-reject scan runs in the filter kernel's prologue (one wave),
-// so a whole verification is three back-to-back launches: row statistics, filter, select.
+// so a whole verification is three back-to-back launches: row statistics, filter, select; two when
+// a row is split into at most two chunks (sample_select_kernel: filter and select in one).
 #pragma once
 
 #include "decide.h"
@@ -163,35 +164,42 @@ __device__ __forceinline__ int lanes_below(unsigned long long mask) {
                                         __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
 }
 
-template <typename DT>
-__global__ __launch_bounds__(kBlock) void sample_kernel(Problem p) {
+// The filter of chunk s = blockIdx.x * G + g of sequence blockIdx.y, by sub-block g (512 threads)
+// of a workgroup of G * 512 threads.  With G > 1 a workgroup filters G chunks of one row side by
+// side; the sub-blocks share nothing but the accept length and the barriers.
+template <typename DT, int G>
+__device__ __forceinline__ void sample_body(const Problem& p) {
   constexpr int kPer = DT::kPerVec;
   constexpr int kVecs = kSampleLaneElems / kPer;  // 16-byte loads per lane and tile
   constexpr int kTile = kSampleTileElems;
   constexpr int kQueueCap = 2 * kWave;  // drained as soon as it holds a full batch
   using storage = typename DT::storage;
 
-  __shared__ int sh_queue[kWavesPerBlock][kQueueCap];    // queued vocabulary indices ...
-  __shared__ int sh_queue_h[kWavesPerBlock][kQueueCap];  // ... and their coarse noise bytes
-  __shared__ int sh_surv_v[kWavesPerBlock][kSurvivorCap];
-  __shared__ float sh_surv_s[kWavesPerBlock][kSurvivorCap];
-  __shared__ float sh_theta[kWavesPerBlock];
-  __shared__ int sh_n, sh_count, sh_overflow;
+  constexpr int kWaves = G * kWavesPerBlock;               // waves of the whole workgroup
+  __shared__ int sh_queue[kWaves][kQueueCap];              // queued vocabulary indices ...
+  __shared__ int sh_queue_h[kWaves][kQueueCap];            // ... and their coarse noise bytes
+  __shared__ int sh_surv_v[kWaves][kSurvivorCap];
+  __shared__ float sh_surv_s[kWaves][kSurvivorCap];
+  __shared__ float sh_theta[kWaves];
+  __shared__ int sh_n, sh_count_g[G], sh_overflow_g[G];
 
-  const int tid = (int)threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
-  const int s = (int)blockIdx.x, b = (int)blockIdx.y;
+  const int g = (int)threadIdx.x / kBlock;                 // sub-block, uniform over a wave
+  const int tid = (int)threadIdx.x - g * kBlock, lane = tid & (kWave - 1);
+  const int wave = (int)threadIdx.x / kWave;               // index into the per-wave arrays
+  const int wave_g = tid / kWave;                          // wave within the sub-block
+  const int s = (int)blockIdx.x * G + g, b = (int)blockIdx.y;
   const int V = p.V;
 
   // ---- accept length of this sequence ---------------------------------------------------------
   const int Kb = seq_len(p, b);
-  if (tid == 0) { sh_count = 0; sh_overflow = 0; }
+  if (tid == 0) { sh_count_g[g] = 0; sh_overflow_g[g] = 0; }
   if (p.decide_fused) {
     // the statistics kernel left one decision per position; scan them for the first rejection
     if (wave == 0) {
       const int nn = first_reject_scan(p, b, lane, true, s == 0);
       if (lane == 0) sh_n = nn;
     }
-  } else if (tid == 0) {
+  } else if (threadIdx.x == 0) {
     const int nn = p.accept_len[b];
     sh_n = nn < 0 ? 0 : (nn > Kb ? Kb : nn);
   }
@@ -349,7 +357,7 @@ __global__ __launch_bounds__(kBlock) void sample_kernel(Problem p) {
   // warm start: a first threshold from 64 elements of this wave's part of the chunk (their loads
   // travel together with the first tile's)
   {
-    const int v = v_begin + wave * kWave + lane;
+    const int v = v_begin + wave_g * kWave + lane;
     float s_up, s_lo;
     evaluate(v, -1, v < v_end, s_up, s_lo);
     theta = fmaxf(theta, wave_max(s_lo));
@@ -407,9 +415,9 @@ __global__ __launch_bounds__(kBlock) void sample_kernel(Problem p) {
   // ---- merge the four waves into this chunk's record -------------------------------------------
   if (lane == 0) sh_theta[wave] = theta;
   __syncthreads();
-  float theta_wg = sh_theta[0];
+  float theta_wg = sh_theta[g * kWavesPerBlock];
 #pragma unroll
-  for (int w = 1; w < kWavesPerBlock; ++w) theta_wg = fmaxf(theta_wg, sh_theta[w]);
+  for (int w = 1; w < kWavesPerBlock; ++w) theta_wg = fmaxf(theta_wg, sh_theta[g * kWavesPerBlock + w]);
   uint32_t* rec = p.records + ((size_t)b * p.S + s) * kRecordWords;
   {
     const bool have = lane < scount;
@@ -418,7 +426,7 @@ __global__ __launch_bounds__(kBlock) void sample_kernel(Problem p) {
     const bool keep = have && su >= theta_wg;
     const unsigned long long km = __ballot(keep);
     int base = 0;
-    if (lane == 0 && km != 0ull) base = atomicAdd(&sh_count, __popcll(km));
+    if (lane == 0 && km != 0ull) base = atomicAdd(&sh_count_g[g], __popcll(km));
     base = __shfl(base, 0, 64);
     if (keep) {
       const int slot = base + lanes_below(km);
@@ -427,13 +435,19 @@ __global__ __launch_bounds__(kBlock) void sample_kernel(Problem p) {
         rec[3 + 2 * slot] = __float_as_uint(su);
       }
     }
-    if (overflow && lane == 0) sh_overflow = 1;
+    if (overflow && lane == 0) sh_overflow_g[g] = 1;
   }
   __syncthreads();
   if (tid == 0) {
     rec[0] = __float_as_uint(theta_wg);
-    rec[1] = (sh_overflow || sh_count > kRecordCap) ? (uint32_t)kRecordOverflow : (uint32_t)sh_count;
+    rec[1] = (sh_overflow_g[g] || sh_count_g[g] > kRecordCap) ? (uint32_t)kRecordOverflow
+                                                            : (uint32_t)sh_count_g[g];
   }
+}
+
+template <typename DT>
+__global__ __launch_bounds__(kBlock) void sample_kernel(Problem p) {
+  sample_body<DT, 1>(p);
 }
 
 // Level 3.  One workgroup per sequence reads the chunk records of the filter kernel.  A single
@@ -441,12 +455,11 @@ __global__ __launch_bounds__(kBlock) void sample_kernel(Problem p) {
 // bounds could not separate are scanned in fp64.  In the common case everything this kernel needs
 // (accept length, chunk headers, survivor entries) is requested in one round of loads.
 template <typename DT>
-__global__ __launch_bounds__(kBlock) void select_kernel(Problem p) {
+__device__ __forceinline__ void select_body(const Problem& p, int b) {
   using storage = typename DT::storage;
   __shared__ float sh_theta[kWavesPerBlock];
   __shared__ int sh_any_overflow, sh_total, sh_only;
   const int tid = (int)threadIdx.x;
-  const int b = (int)blockIdx.x;
   const int V = p.V;
   const uint32_t* recs = p.records + (size_t)b * p.S * kRecordWords;
   const int total = p.S * kRecordCap;
@@ -609,6 +622,26 @@ __global__ __launch_bounds__(kBlock) void select_kernel(Problem p) {
       best = block_best(exact_scan<DT>(ctx, 0, V, kModeTargetFallback, Best{-INFINITY, -1}));
   }
   if (tid == 0) p.out_tokens[r0 + b + n] = best.v;
+}
+
+template <typename DT>
+__global__ __launch_bounds__(kBlock) void select_kernel(Problem p) {
+  select_body<DT>(p, (int)blockIdx.x);
+}
+
+// Filter and exact choice in one launch, for rows that are split into G <= 2 chunks: a workgroup of
+// G * 512 threads filters all chunks of its row, then its first 512 threads read the records it
+// has just written (visible within the workgroup after the barrier) and choose.  Saves a launch
+// and the dependent start of a second kernel.  Registers: the single-chunk bf16 variant is held to
+// 80 (three 512-thread groups per CU, as the filter alone); the others run one or two groups per
+// CU whatever they use.
+template <typename DT, int G>
+__global__ __launch_bounds__(kBlock* G, (G == 1 && sizeof(typename DT::storage) == 2) ? 6 : 4)
+void sample_select_kernel(Problem p) {
+  sample_body<DT, G>(p);
+  __syncthreads();
+  if ((int)threadIdx.x >= kBlock) return;  // whole waves
+  select_body<DT>(p, (int)blockIdx.y);
 }
 
 }  // namespace ears
