@@ -121,8 +121,10 @@ int ears_verify_bf16(const void* target_logits, const void* draft_logits,
                      void* stream);
 
 /* ---------------------------------------------------------------------------------------------
- * Ragged batch: per-sequence draft length K_b >= 1, temperature and beta (the gathered
- * "active sequences" layout of Section 3.3 item 3).
+ * Ragged batch: per-sequence draft length K_b >= 0, temperature and beta (the gathered
+ * "active sequences" layout of Section 3.3 item 3).  A sequence without draft tokens (K_b = 0)
+ * has one target row and gets accept length 0 and a token drawn from that row; the batch as a
+ * whole needs at least one draft row.
  *   row_offsets      [B+1] int64, device; CSR over the packed DRAFT rows: sequence b owns draft
  *                    rows row_offsets[b] .. row_offsets[b+1); row_offsets[0] = 0
  *   total_draft_rows host value of row_offsets[B] (the caller sized its buffers with it)

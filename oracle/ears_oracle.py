@@ -213,7 +213,7 @@ def verify_ragged(target: np.ndarray, draft: np.ndarray, tokens: np.ndarray,
     B = row_offsets.shape[0] - 1
     R = int(row_offsets[-1])
     V = target.shape[1]
-    assert row_offsets[0] == 0 and np.all(np.diff(row_offsets) >= 1)
+    assert row_offsets[0] == 0 and np.all(np.diff(row_offsets) >= 0)
     assert target.shape == (R + B, V) and draft.shape == (R, V) and tokens.shape == (R,)
     assert T.shape == (B,) and beta.shape == (B,)
     if seq_ids is not None:

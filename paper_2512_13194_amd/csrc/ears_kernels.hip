@@ -66,7 +66,7 @@ static void sample_split(int B, int V, int elems_per_tile, int* S, int* chunk) {
 }
 
 static bool workspace_layout(int64_t R, int B, int V, WorkspaceLayout* w) {
-  if (R < 1 || B < 1 || V < 1 || R < B || R > (int64_t)0x3FFFFFFF) return false;
+  if (R < 1 || B < 1 || V < 1 || R > (int64_t)0x3FFFFFFF) return false;
   int S4, chunk;
   sample_split(B, V, kSampleTileElems, &S4, &chunk);
   size_t o = 0;
@@ -340,8 +340,7 @@ void ears_release(void) {
 }
 
 size_t ears_greedy_workspace_bytes(int64_t total_draft_rows, int B) {
-  if (total_draft_rows < 1 || B < 1 || total_draft_rows < B ||
-      total_draft_rows > (int64_t)0x3FFFFFFF)
+  if (total_draft_rows < 1 || B < 1 || total_draft_rows > (int64_t)0x3FFFFFFF)
     return 0;
   return align_up((size_t)(total_draft_rows + B) * sizeof(int32_t), 256);
 }

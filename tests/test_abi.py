@@ -46,7 +46,7 @@ def test_workspace_bytes(L):
     assert binding.ears_workspace_bytes(0, 1, 8) == 0
     assert binding.ears_workspace_bytes(8, 0, 8) == 0
     assert binding.ears_workspace_bytes(8, 1, 0) == 0
-    assert binding.ears_workspace_bytes(3, 4, 8) == 0      # fewer rows than sequences
+    assert binding.ears_workspace_bytes(3, 4, 8) > 0       # fewer rows than sequences: some have no draft token
 
 
 P = 0x10000   # a 256-byte aligned stand-in address; never dereferenced on these paths
@@ -88,7 +88,7 @@ def test_ex_argument_errors(L):
     assert _ex(L, dtype=2) == b.EARS_ERR_DTYPE
     assert _ex(L, dtype=-1) == b.EARS_ERR_DTYPE
     assert _ex(L, R=7) == b.EARS_ERR_SHAPE                 # rectangular: R must be B*K
-    assert _ex(L, off=P, R=1, B=2) == b.EARS_ERR_SHAPE     # ragged: at least one row per sequence
+    assert _ex(L, off=P, R=0, B=2) == b.EARS_ERR_SHAPE     # ragged: at least one draft row in all
     assert _ex(L, stages=0) == b.EARS_ERR_PARAM
     assert _ex(L, stages=8) == b.EARS_ERR_PARAM
     assert _ex(L, unc=3) == b.EARS_ERR_PARAM
@@ -148,7 +148,7 @@ def test_greedy_argument_errors(L):
     from paper_2512_13194_amd import binding as b
     assert b.ears_greedy_workspace_bytes(2048, 256) == (2048 + 256) * 4
     assert b.ears_greedy_workspace_bytes(7, 3) % 256 == 0
-    assert b.ears_greedy_workspace_bytes(0, 1) == 0 and b.ears_greedy_workspace_bytes(2, 3) == 0
+    assert b.ears_greedy_workspace_bytes(0, 1) == 0 and b.ears_greedy_workspace_bytes(2, 3) == 256
     assert _greedy(L, dtype=2) == b.EARS_ERR_DTYPE
     assert _greedy(L, target=None) == b.EARS_ERR_NULL
     assert _greedy(L, tokens=None) == b.EARS_ERR_NULL
@@ -158,7 +158,7 @@ def test_greedy_argument_errors(L):
     assert _greedy(L, V=0) == b.EARS_ERR_SHAPE
     assert _greedy(L, K=0) == b.EARS_ERR_SHAPE
     assert _greedy(L, R=7) == b.EARS_ERR_SHAPE              # rectangular: R must be B*K
-    assert _greedy(L, off=P, R=1, B=2) == b.EARS_ERR_SHAPE  # fewer rows than sequences
+    assert _greedy(L, off=P, R=0, B=2) == b.EARS_ERR_SHAPE  # no draft row at all
     assert _greedy(L, target=P + 8) == b.EARS_ERR_ALIGN
     assert _greedy(L, tokens=P + 2) == b.EARS_ERR_ALIGN
     assert _greedy(L, off=P + 4) == b.EARS_ERR_ALIGN

@@ -70,6 +70,25 @@ def test_greedy_target_buffer_larger_than_4_gib(ears, oracle):
     assert 0 < acc.sum() < B * K
 
 
+def test_greedy_ragged_with_sequences_without_draft_tokens(ears, oracle):
+    from paper_2512_13194_amd import inputs
+    _log("greedy ragged with empty sequences")
+    batch = inputs.make_ragged(50, 2500, torch.bfloat16, data_seed=88, K_lo=0, K_hi=2, device="cuda")
+    off = batch.row_offsets.cpu().numpy()
+    assert (np.diff(off) == 0).sum() > 8
+    tokens = batch.tokens.clone()
+    top = batch.target.float().argmax(-1).to(torch.int32)
+    for b in range(50):
+        r0, r1 = int(off[b]), int(off[b + 1])
+        if r1 > r0 and b % 2 == 0:
+            tokens[r0:r1] = top[r0 + b:r1 + b]
+    acc, out = ears.ears_verify_greedy(batch.target, tokens, row_offsets=batch.row_offsets)
+    torch.cuda.synchronize()
+    o_acc, o_out, _ = oracle.verify_greedy(inputs.logits_to_numpy(batch.target), tokens.cpu().numpy(), off)
+    assert np.array_equal(acc.cpu().numpy(), o_acc) and np.array_equal(out.cpu().numpy(), o_out)
+    assert (o_acc[np.diff(off) == 0] == 0).all()
+
+
 def test_greedy_ties_masked_rows_and_bad_tokens(ears, oracle):
     _log("greedy ties / masked")
     V, B, K = 5000, 6, 3

@@ -458,6 +458,27 @@ def test_ragged_small(ears, oracle):
         assert rep.exempt_decisions == 0 and rep.exempt_tokens == 0
 
 
+def test_ragged_with_sequences_without_draft_tokens(ears, oracle):
+    """K_b = 0 for some sequences (also the first and the last of the batch): accept length 0 and a
+    token from their only target row; fewer draft rows than sequences is a valid batch."""
+    from paper_2512_13194_amd import inputs
+    _log("ragged with empty sequences")
+    for dtype, V, B, seed in ((torch.bfloat16, 9000, 60, 85), (torch.float32, 700, 300, 86)):
+        batch = inputs.make_ragged(B, V, dtype, data_seed=seed, K_lo=0, K_hi=2, device="cuda")
+        off = batch.row_offsets.cpu().numpy()
+        empty = np.diff(off) == 0
+        assert empty.sum() > B // 5
+        for uncertainty in (0, 1):
+            rep, ora, out = run_ragged(ears, oracle, batch, 16, uncertainty=uncertainty)
+            assert rep.exempt_decisions == 0 and rep.exempt_tokens == 0
+            assert (out["accept_len"].cpu().numpy()[empty] == 0).all()
+    # a batch with fewer draft rows than sequences
+    batch = inputs.make_ragged(40, 2000, torch.bfloat16, data_seed=87, K_lo=0, K_hi=1, device="cuda")
+    assert batch.total_draft_rows < 40
+    rep, _, _ = run_ragged(ears, oracle, batch, 17)
+    assert rep.exempt_decisions == 0 and rep.exempt_tokens == 0
+
+
 def test_output_law_on_gpu(ears):
     """V = 8, K = 1, beta = 0: the emitted token follows P_target (chi-square), on the GPU path."""
     from scipy import stats

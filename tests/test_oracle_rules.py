@@ -586,3 +586,34 @@ def test_variance_uncertainty_limits_order_and_acceptance_rate(oracle):
     assert stats.binomtest(int((r.accept_len == 1).sum()), N, want).pvalue > 1e-4
     want_mp = min(1.0, pt[x] / pd[x] + beta * (1.0 - pt.max()))
     assert stats.binomtest(int((r.accept_len == 1).sum()), N, want_mp).pvalue < 1e-6
+
+
+def test_sequence_without_draft_tokens(oracle):
+    """K_b = 0 in a ragged batch: accept length 0 and the token is the Gumbel-max draw from the
+    sequence's only target row with the noise of position 0 (written out here with numpy)."""
+    rng = np.random.default_rng(70)
+    V, seed = 300, 12
+    off = np.array([0, 2, 2, 3, 3, 3, 5], dtype=np.int64)          # K_b = 2, 0, 1, 0, 0, 2
+    B, R = 6, 5
+    target = (rng.standard_normal((R + B, V)) * 2).astype(np.float32)
+    draft = (target[[0, 1, 3, 6, 7]] + rng.standard_normal((R, V))).astype(np.float32)
+    tokens = rng.integers(0, V, R).astype(np.int32)
+    T = np.array([1.0, 0.7, 1.3, 0.5, 2.0, 1.0], dtype=np.float32)
+    beta = np.full(B, 0.2, dtype=np.float32)
+    ids = np.array([5, 900, 7, 2 ** 40 + 3, 11, 13], dtype=np.int64)
+    r = oracle.verify_ragged(target, draft, tokens, off, T, beta, seed, seq_ids=ids)
+    for b in (1, 3, 4):
+        row = target[off[b] + b].astype(np.float64)
+        g = np.array([oracle.gumbel(seed, int(ids[b]), 0, v) for v in range(V)])
+        assert r.accept_len[b] == 0
+        assert r.tokens[off[b] + b] == int(np.argmax(row / float(T[b]) + g))
+    # the other sequences are what they are without the empty ones around them
+    keep = np.array([0, 2, 5])
+    t2 = np.concatenate([target[off[b] + b: off[b + 1] + b + 1] for b in keep])
+    d2 = np.concatenate([draft[off[b]: off[b + 1]] for b in keep])
+    k2 = np.concatenate([tokens[off[b]: off[b + 1]] for b in keep])
+    off2 = np.array([0, 2, 3, 5], dtype=np.int64)
+    r2 = oracle.verify_ragged(t2, d2, k2, off2, T[keep], beta[keep], seed, seq_ids=ids[keep])
+    assert np.array_equal(r2.accept_len, r.accept_len[keep])
+    for i, b in enumerate(keep):
+        assert np.array_equal(r2.tokens[off2[i] + i: off2[i + 1] + i + 1], r.tokens[off[b] + b: off[b + 1] + b + 1])
