@@ -53,7 +53,9 @@ struct Problem {
   uint32_t* records;    // [B, S, kRecordWords]
   int S;                // chunks per row
   int chunk;            // vocabulary entries per chunk (a multiple of the tile size)
-  int decide_fused;     // statistics kernel decides each position; the filter kernel scans them
+  int decide_fused;     // where the filter kernel finds the accept length: 0 in accept_len (an earlier
+                        // DECIDE stage left it), 1 by scanning the decisions the statistics kernel
+                        // left, 2 by deciding each position itself from the cached statistics
   // outputs
   int32_t* accept_len;
   int32_t* out_tokens;

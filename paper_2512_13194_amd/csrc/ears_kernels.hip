@@ -110,6 +110,23 @@ static int validate(int dtype, const void* target, const void* draft, const int3
   return EARS_OK;
 }
 
+// The sampling stage: filter and exact choice in one launch when a row is split into one or two
+// chunks, otherwise one launch each.
+template <typename DT, bool kLate>
+static void launch_sample(const Problem& p, hipStream_t stream) {
+  if (p.S == 1) {
+    hipLaunchKernelGGL((sample_select_kernel<DT, 1, kLate>), dim3(1u, (unsigned)p.B), dim3(kBlock), 0,
+                       stream, p);
+  } else if (p.S == 2) {
+    hipLaunchKernelGGL((sample_select_kernel<DT, 2, kLate>), dim3(1u, (unsigned)p.B), dim3(2 * kBlock),
+                       0, stream, p);
+  } else {
+    hipLaunchKernelGGL((sample_kernel<DT, kLate>), dim3((unsigned)p.S, (unsigned)p.B), dim3(kBlock), 0,
+                       stream, p);
+    hipLaunchKernelGGL((select_kernel<DT>), dim3((unsigned)p.B), dim3(kBlock), 0, stream, p);
+  }
+}
+
 template <typename DT>
 static int launch(Problem p, int stages, hipStream_t stream) {
   sample_split(p.B, p.V, kSampleTileElems, &p.S, &p.chunk);
@@ -117,10 +134,13 @@ static int launch(Problem p, int stages, hipStream_t stream) {
   const bool decide = (stages & EARS_STAGE_DECIDE) != 0;
   const bool sample = (stages & EARS_STAGE_SAMPLE) != 0;
   // All three stages in one call: the statistics kernel decides each position as it finishes it
-  // and the filter kernel's prologue scans the decisions for the first rejection.  Otherwise a
-  // small kernel decides and scans from the cached statistics.
+  // and the filter kernel's prologue scans the decisions for the first rejection.  DECIDE and
+  // SAMPLE on cached statistics: the filter kernel's prologue takes the decisions itself.  DECIDE
+  // on its own: a small kernel decides and scans.
   const bool fused = stats && decide && sample;
-  p.decide_fused = fused ? 1 : 0;
+  // DECIDE and SAMPLE on statistics cached earlier: the filter kernel's prologue decides
+  const bool late = !stats && decide && sample;
+  p.decide_fused = fused ? 1 : (late ? 2 : 0);
   if (stats) {
     const dim3 grid((unsigned)p.R), block(kBlock);
     if (fused) {
@@ -139,23 +159,13 @@ static int launch(Problem p, int stages, hipStream_t stream) {
         hipLaunchKernelGGL((row_stats_kernel<DT, 4, false, kMeasureNone>), grid, block, 0, stream, p);
     }
   }
-  if (decide && !fused) {
+  if (decide && !fused && !late) {
     hipLaunchKernelGGL(decide_kernel, dim3((unsigned)((p.B + kWavesPerBlock - 1) / kWavesPerBlock)),
                        dim3(kBlock), 0, stream, p);
   }
   if (sample) {
-    // rows split into one or two chunks: filter and exact choice in one launch
-    if (p.S == 1) {
-      hipLaunchKernelGGL((sample_select_kernel<DT, 1>), dim3(1u, (unsigned)p.B), dim3(kBlock), 0,
-                         stream, p);
-    } else if (p.S == 2) {
-      hipLaunchKernelGGL((sample_select_kernel<DT, 2>), dim3(1u, (unsigned)p.B), dim3(2 * kBlock), 0,
-                         stream, p);
-    } else {
-      hipLaunchKernelGGL((sample_kernel<DT>), dim3((unsigned)p.S, (unsigned)p.B), dim3(kBlock), 0,
-                         stream, p);
-      hipLaunchKernelGGL((select_kernel<DT>), dim3((unsigned)p.B), dim3(kBlock), 0, stream, p);
-    }
+    if (late) launch_sample<DT, true>(p, stream);
+    else launch_sample<DT, false>(p, stream);
   }
   return hipGetLastError() == hipSuccess ? EARS_OK : EARS_ERR_HIP;
 }

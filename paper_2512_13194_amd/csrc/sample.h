@@ -167,7 +167,9 @@ __device__ __forceinline__ int lanes_below(unsigned long long mask) {
 // The filter of chunk s = blockIdx.x * G + g of sequence blockIdx.y, by sub-block g (512 threads)
 // of a workgroup of G * 512 threads.  With G > 1 a workgroup filters G chunks of one row side by
 // side; the sub-blocks share nothing but the accept length and the barriers.
-template <typename DT, int G>
+// kLate: the decisions are taken here, from the cached statistics (a DECIDE | SAMPLE call); kept
+// out of the other instantiations because the fp64 decision raises the register count.
+template <typename DT, int G, bool kLate>
 __device__ __forceinline__ void sample_body(const Problem& p) {
   constexpr int kPer = DT::kPerVec;
   constexpr int kVecs = kSampleLaneElems / kPer;  // 16-byte loads per lane and tile
@@ -194,9 +196,10 @@ __device__ __forceinline__ void sample_body(const Problem& p) {
   const int Kb = seq_len(p, b);
   if (tid == 0) { sh_count_g[g] = 0; sh_overflow_g[g] = 0; }
   if (p.decide_fused) {
-    // the statistics kernel left one decision per position; scan them for the first rejection
+    // one decision per position, left by the statistics kernel or taken here from the cached
+    // statistics; the first rejection is the accept length
     if (wave == 0) {
-      const int nn = first_reject_scan(p, b, lane, true, s == 0);
+      const int nn = first_reject_scan(p, b, lane, !kLate, s == 0);
       if (lane == 0) sh_n = nn;
     }
   } else if (threadIdx.x == 0) {
@@ -445,9 +448,9 @@ __device__ __forceinline__ void sample_body(const Problem& p) {
   }
 }
 
-template <typename DT>
+template <typename DT, bool kLate>
 __global__ __launch_bounds__(kBlock) void sample_kernel(Problem p) {
-  sample_body<DT, 1>(p);
+  sample_body<DT, 1, kLate>(p);
 }
 
 // Level 3.  One workgroup per sequence reads the chunk records of the filter kernel.  A single
@@ -635,10 +638,10 @@ __global__ __launch_bounds__(kBlock) void select_kernel(Problem p) {
 // and the dependent start of a second kernel.  Registers: the single-chunk bf16 variant is held to
 // 80 (three 512-thread groups per CU, as the filter alone); the others run one or two groups per
 // CU whatever they use.
-template <typename DT, int G>
-__global__ __launch_bounds__(kBlock* G, (G == 1 && sizeof(typename DT::storage) == 2) ? 6 : 4)
+template <typename DT, int G, bool kLate>
+__global__ __launch_bounds__(kBlock* G, (G == 1 && !kLate && sizeof(typename DT::storage) == 2) ? 6 : 4)
 void sample_select_kernel(Problem p) {
-  sample_body<DT, G>(p);
+  sample_body<DT, G, kLate>(p);
   __syncthreads();
   if ((int)threadIdx.x >= kBlock) return;  // whole waves
   select_body<DT>(p, (int)blockIdx.y);
