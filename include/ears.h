@@ -7,7 +7,7 @@
  * p_d = softmax(draft_logits[b,i,:] / T), x = draft_tokens[b,i]:
  *
  *   uncertainty  unc = 1 - max_v p_t(v)                         (paper Section 3.2)
- *   tolerance    Tol = beta * unc                               (Section 3.2, "Dynamic Tolerance")
+ *   tolerance    Tol = beta * unc                               (Section 3.2, the dynamic tolerance)
  *   ratio        R   = p_t(x) / max(p_d(x), 1e-10)              (Section 3.2 step 2; guard 3.3.2)
  *   threshold    thr = max(U - Tol, 0),  U ~ Uniform[0,1)       (Section 3.2 step 3; clamp 3.3.2)
  *   accept x  iff  R >= thr                                     (Section 3.2 step 5)
@@ -20,8 +20,8 @@
  * Philox4x32-10 noise keyed on (seed, sequence id, position, vocabulary index), so a call is a
  * pure function of its arguments.  max_v p_t(v) is obtained in the same single pass over the row
  * that yields p_t(x) (max p = 1/Z with Z the sum of exp((l - max l)/T)); the per-row statistics
- * are kept in the workspace and re-used by the sampling pass, which is the "pre-computation and
- * delayed lookup" of Section 3.3 item 1.
+ * are kept in the workspace and re-used by the sampling pass: computed once ahead of time and
+ * looked up later, as Section 3.3 item 1 asks.
  *
  * Conventions
  *  - Every pointer is a DEVICE pointer on the current HIP device unless marked "host".
@@ -76,8 +76,8 @@ enum {
 };
 
 /* Uncertainty measure that scales the tolerance.  MAXPROB is the paper's 1 - max_v p_t(v)
- * (Section 3.2).  The other two are the "more refined uncertainty measures" the paper's Section 5
- * names without formulas: ENTROPY is the normalised Shannon entropy H(p_t) / log V, VARIANCE the
+ * (Section 3.2).  The other two are the finer measures that the paper's Section 5 leaves to
+ * future work, without formulas: ENTROPY is the normalised Shannon entropy H(p_t) / log V, VARIANCE the
  * total variance sum_v p_t(v) (1 - p_t(v)) = 1 - sum_v p_t(v)^2 of the one-hot outcome drawn from
  * p_t (in [0, 1 - 1/V], never below the MAXPROB measure).  Each comes out of the same single pass
  * over the row. */
@@ -122,7 +122,7 @@ int ears_verify_bf16(const void* target_logits, const void* draft_logits,
 
 /* ---------------------------------------------------------------------------------------------
  * Ragged batch: per-sequence draft length K_b >= 0, temperature and beta (the gathered
- * "active sequences" layout of Section 3.3 item 3).  A sequence without draft tokens (K_b = 0)
+ * layout of the sequences still active, Section 3.3 item 3).  A sequence without draft tokens (K_b = 0)
  * has one target row and gets accept length 0 and a token drawn from that row; the batch as a
  * whole needs at least one draft row.
  *   row_offsets      [B+1] int64, device; CSR over the packed DRAFT rows: sequence b owns draft
@@ -210,8 +210,8 @@ int ears_verify_greedy(int dtype, const void* target_logits, const int32_t* draf
                        int32_t* out_tokens, void* stream);
 
 /* ---------------------------------------------------------------------------------------------
- * Producer-side fusion (Section 3.3 item 1: max P_t is computed "immediately after the target
- * model's forward pass" and cached).  The last step of that pass, the vocabulary projection
+ * Producer-side fusion (Section 3.3 item 1 has max P_t computed right behind the target
+ * model's forward pass and cached).  The last step of that pass, the vocabulary projection
  *   logits[n, v] = sum_k hidden[n, k] * weight[v, k]      (bf16 inputs, fp32 accumulation, MFMA)
  * is computed here with an epilogue that rounds each logit to bf16 (nearest even), writes it once,
  * and takes the statistics of the ROUNDED row at temperature T while it is still in registers:
@@ -238,7 +238,7 @@ int ears_lm_head_bf16(const void* hidden, const void* weight, int N, int D, int 
 /* The same per-row statistics for logits that already exist: one streaming pass over the rows of
  * ONE matrix, [rows, V] row-major (16-byte aligned base), at temperature T (scalar, or per row when
  * row_temperature is not NULL).  A pipeline can run it on the draft logits as soon as the draft
- * model has produced them, and on the target logits after the target pass ("pre-computation",
+ * model has produced them, and on the target logits after the target pass (the computing ahead of time of
  * Section 3.3 item 1), and hand both to ears_import_stats().
  *   out_row_max [rows] float, out_row_sumexp [rows] double, out_row_entropy [rows] double or NULL
  *   (Shannon entropy in nats, for the entropy-based uncertainty measure) */

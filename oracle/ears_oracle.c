@@ -81,7 +81,7 @@ static const void* row_ptr(const void* base, int dtype, int64_t row, int V) {
   return (const char*)base + (size_t)row * (size_t)V * esz;
 }
 
-/* "the full distribution over the vocabulary" (Section 3.1), at sampling temperature T
+/* The whole distribution over the vocabulary that Section 3.1 works with, at sampling temperature T
  * (Section 4.1 uses T = 0.9): p = softmax(l / T), the textbook three passes. */
 double ears_oracle_softmax(const void* row, int dtype, int V, double T, double* p, double* m_out,
                            double* Z_out) {
@@ -168,8 +168,8 @@ int ears_oracle_verify_seq(const void* target_rows, const void* draft_rows, cons
     /* step 3 */
     double U = ears_oracle_accept_uniform(seed, seq_id, (uint32_t)i);
     /* step 4: uncertainty 1 - max P_t and tolerance beta * uncertainty (Section 3.2); the
-     * alternative measure (Section 5, "distribution entropy") is the Shannon entropy of P_t
-     * divided by its largest possible value log V; the other one it names ("variance") is taken
+     * alternative measure (Section 5 names the entropy of the distribution) is the Shannon entropy of P_t
+     * divided by its largest possible value log V; the other one it names, the variance, is taken
      * as the total variance of the one-hot outcome, sum_v P_t(v) (1 - P_t(v)) */
     double unc = 1.0 - maxpt;
     if (unc_mode == EARS_ORACLE_UNC_ENTROPY) unc = (V > 1) ? ears_oracle_entropy(pt, V) / log((double)V) : 0.0;

@@ -5,13 +5,13 @@
  * product path may call it; it shares no source, header, table or helper with the GPU code.
  *
  * Every function is sequential fp64 arithmetic written in the order of the paper's Section 3.2
- * ("Algorithm Logic", steps 1-5), with the two guards of Section 3.3 item 2 and the
+ * (its five steps), with the two guards of Section 3.3 item 2 and the
  * first-rejection rule of Section 3.1.  The replacement token at the rejected slot is drawn from
  * the residual distribution norm(max(0, p_t - p_d)) of the standard speculative sampling scheme
  * that the paper takes as its baseline (its references [1], [2]); the bonus token, when every
  * draft token is accepted, is drawn from the target row after the last draft position.
  *
- * Randomness: the paper only says "sample U_i ~ Uniform(0,1)".  Both the oracle and the GPU
+ * Randomness: the paper only says that U_i is drawn uniformly from (0, 1).  Both the oracle and the GPU
  * library implement, independently, the published counter-based generator Philox4x32-10
  * (Salmon, Moraes, Dror, Shaw: "Parallel random numbers: as easy as 1, 2, 3", SC'11) with the
  * keying documented at ears_oracle_philox_word below.
@@ -53,8 +53,8 @@ extern "C" {
 #define EARS_ORACLE_NSAMP 4
 
 /* uncertainty measure that scales the tolerance: the paper's 1 - max P_t (Section 3.2), the
- * normalised Shannon entropy H(P_t) / log V (the "distribution entropy" of Section 5), or the
- * total variance sum_v P_t(v) (1 - P_t(v)) of the one-hot outcome (the "variance" of Section 5,
+ * normalised Shannon entropy H(P_t) / log V (the entropy of the distribution, which Section 5 names), or the
+ * total variance sum_v P_t(v) (1 - P_t(v)) of the one-hot outcome (the variance that Section 5 names,
  * which the paper does not define further) */
 /* Support of the residual distribution norm(max(0, p_t - p_d)): an entry belongs to it when
  * p_t(v) - p_d(v) exceeds this fraction of p_t(v) + p_d(v).  2^-40 is far above the rounding noise

@@ -1,5 +1,5 @@
-// Producer-side fusion (paper Section 3.3 item 1: the statistics are computed "immediately after the
-// target model's forward pass"): the vocabulary projection logits[n, v] = sum_k hidden[n, k] *
+// Producer-side fusion (paper Section 3.3 item 1 has the statistics computed right behind the target
+// model's forward pass): the vocabulary projection logits[n, v] = sum_k hidden[n, k] *
 // weight[v, k] on the matrix cores, whose epilogue rounds the logits to bf16, takes the softmax
 // statistics (row maximum, sum of exponentials) of the rounded values while they are still in
 // registers, and writes the logits once.  The verification step then starts from cached statistics
