@@ -208,6 +208,22 @@ def main() -> int:
         "frac": lm_flop / (lm_ms * 1e-3) / 1e12 / 2500.0}
     del hidden, weight, lm_ws, lm_logits
 
+    # the same shape with four times the sequences: what the fixed costs of the headline batch weigh
+    big = inputs.make_config(WORKLOAD_INDEX, device="cuda", scale_B=4 * B)   # same recipe
+    big_ws = torch.empty(ears.ears_workspace_bytes(4 * B * K, 4 * B, V), dtype=torch.uint8, device="cuda")
+    big_acc = torch.empty(4 * B, dtype=torch.int32, device="cuda")
+    big_tok = torch.empty(4 * B * (K + 1), dtype=torch.int32, device="cuda")
+    big_ms = timed_ms(lambda: ears.ears_verify_ex(
+        big.target, big.draft, big.tokens, temperature=T, beta=betas[1], seed=seed0, workspace=big_ws,
+        out_accept_len=big_acc, out_tokens=big_tok), reps=10)
+    big_rej = int((big_acc < K).sum().item())
+    big_bytes = (2 * 4 * B * K + 2 * big_rej + (4 * B - big_rej)) * V * esz
+    other_paths["four_times_the_batch"] = {
+        "B": 4 * B, "ms_per_call": big_ms, "positions_per_s": 4 * B * K / (big_ms * 1e-3),
+        "algorithmic_bytes": big_bytes, "achieved_GBps": big_bytes / (big_ms * 1e-3) / 1e9,
+        "frac_of_hbm_peak": big_bytes / (big_ms * 1e-3) / 1e9 / 8000.0}
+    del big, big_ws
+
     if args.traffic_calibration:
         # plain copy of the draft buffer: reads and writes exactly draft.numel() * 2 bytes
         dst = torch.empty_like(batch.draft)
