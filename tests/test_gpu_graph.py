@@ -68,3 +68,71 @@ def test_captured_call_replays_like_eager_and_like_the_oracle(oracle):
         torch.cuda.synchronize()
         return (time.perf_counter() - t0) / n * 1e6
     print("  eager %.1f us/call, graph replay %.1f us/call" % (timed(call), timed(graph.replay)), flush=True)
+
+
+def test_producer_side_pipeline_and_greedy_call_in_one_graph(oracle):
+    """The projection with its statistics, the draft rows' statistics, their import, DECIDE | SAMPLE
+    and a greedy verification, captured together and replayed on new hidden states: every replay
+    equals the same calls made eagerly, and the eager result equals the oracle on the emitted logits."""
+    import paper_2512_13194_amd as ears
+    from paper_2512_13194_amd import inputs
+    ears.lib()
+    print("graph capture: producer-side pipeline", flush=True)
+    B, K, D, V, T, beta, seed = 16, 3, 128, 8192, 0.9, 0.4, 31
+    N = B * (K + 1)
+    g = torch.Generator(device="cuda").manual_seed(3)
+    hidden = torch.randn(N, D, generator=g, device="cuda").to(torch.bfloat16)
+    weight = (torch.randn(V, D, generator=g, device="cuda") * (2.5 / D ** 0.5)).to(torch.bfloat16)
+    draft = (torch.randn(B, K, V, generator=g, device="cuda") * 2.0).to(torch.bfloat16)
+    tokens = torch.randint(0, V, (B, K), generator=g, device="cuda", dtype=torch.int32)
+    logits = torch.empty(N, V, dtype=torch.bfloat16, device="cuda")
+    tm = torch.empty(N, dtype=torch.float32, device="cuda")
+    tz = torch.empty(N, dtype=torch.float64, device="cuda")
+    dm = torch.empty(B * K, dtype=torch.float32, device="cuda")
+    dz = torch.empty(B * K, dtype=torch.float64, device="cuda")
+    lm_ws = torch.empty(ears.ears_lm_head_workspace_bytes(N, V), dtype=torch.uint8, device="cuda")
+    ws = torch.empty(ears.ears_workspace_bytes(B * K, B, V), dtype=torch.uint8, device="cuda")
+    gws = torch.empty(ears.ears_greedy_workspace_bytes(B * K, B), dtype=torch.uint8, device="cuda")
+    acc = torch.empty(B, dtype=torch.int32, device="cuda")
+    tok = torch.empty(N, dtype=torch.int32, device="cuda")
+    gacc = torch.empty(B, dtype=torch.int32, device="cuda")
+    gtok = torch.empty(N, dtype=torch.int32, device="cuda")
+
+    def call():
+        ears.ears_lm_head_bf16(hidden, weight, temperature=T, out_logits=logits, out_row_max=tm,
+                               out_row_sumexp=tz, workspace=lm_ws)
+        ears.ears_row_stats(draft, temperature=T, out_row_max=dm, out_row_sumexp=dz)
+        target = logits.view(B, K + 1, V)
+        ears.ears_import_stats(target, draft, tokens, tm, tz, dm, dz, ws)
+        ears.ears_verify_ex(target, draft, tokens, temperature=T, beta=beta, seed=seed, workspace=ws,
+                            stages=ears.EARS_STAGE_DECIDE | ears.EARS_STAGE_SAMPLE,
+                            out_accept_len=acc, out_tokens=tok)
+        ears.ears_verify_greedy(target, tokens, workspace=gws, out_accept_len=gacc, out_tokens=gtok)
+
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        call()
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        call()
+    torch.cuda.synchronize()
+    for step in range(3):
+        hidden.copy_(torch.randn(N, D, generator=g, device="cuda").to(torch.bfloat16))
+        torch.cuda.synchronize()
+        for t in (acc, tok, gacc, gtok):
+            t.fill_(-7)
+        graph.replay()
+        torch.cuda.synchronize()
+        got = [t.clone() for t in (acc, tok, gacc, gtok, logits)]
+        call()
+        torch.cuda.synchronize()
+        for a, b in zip(got, (acc, tok, gacc, gtok, logits)):
+            assert torch.equal(a, b), step
+        lb = inputs.logits_to_numpy(logits.view(B, K + 1, V))
+        ora = oracle.verify(lb, inputs.logits_to_numpy(draft), tokens.cpu().numpy(), float(np.float32(T)),
+                            float(np.float32(beta)), seed, nthreads=NTHREADS)
+        assert np.array_equal(got[0].cpu().numpy(), ora.accept_len), step
+        assert np.array_equal(got[1].view(B, K + 1).cpu().numpy(), ora.tokens), step
+        o_acc, o_out, _ = oracle.verify_greedy(lb, tokens.cpu().numpy())
+        assert np.array_equal(got[2].cpu().numpy(), o_acc) and np.array_equal(got[3].view(B, K + 1).cpu().numpy(), o_out)
