@@ -125,7 +125,7 @@ def main() -> int:
                             seed=seed0 + i, workspace=ws, stages=ears.EARS_STAGE_STATS,
                             out_accept_len=acc, out_tokens=tok.view(-1))
 
-    for i in range(max(2, args.warmup // 2)):
+    for i in range(max(10, args.warmup)):   # the clock settles within a few launches
         stats_only(i)
     torch.cuda.synchronize()
     k0, k1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
