@@ -21,6 +21,7 @@ from .ears_oracle import (  # noqa: F401
     round_bf16,
     philox4x32_10,
     softmax,
+    top2,
     verify,
     verify_greedy,
     verify_ragged,

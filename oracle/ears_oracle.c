@@ -43,7 +43,7 @@ uint32_t ears_oracle_philox_word(uint64_t seed, uint64_t seq, uint32_t pos, uint
   return out[word & 3u];
 }
 
-/* "Sample U_i ~ Uniform(0,1)" (Section 3.2, step 3): the top 24 bits of one Philox word. */
+/* Acceptance uniform of Section 3.2 step 3: the top 24 bits of one Philox word, in [0, 1). */
 double ears_oracle_accept_uniform(uint64_t seed, uint64_t seq, uint32_t pos) {
   uint32_t w = ears_oracle_philox_word(seed, seq, pos, 0u, 0u, 0u);
   return (double)(w >> 8) * 0x1p-24;
@@ -105,26 +105,51 @@ double ears_oracle_softmax(const void* row, int dtype, int V, double T, double* 
   return pmax;
 }
 
-/* argmax over v of score(v), lowest index on ties; also the runner-up score. */
+/* argmax over v of score(v), lowest index on ties; also the runner-up (the entry that would win
+ * if the winner were taken away: its score and index, again lowest index on ties; index -1 and
+ * score -inf while there is none).  Entries are pushed in increasing index order. */
 typedef struct {
   double best, second;
-  int32_t arg;
+  int32_t arg, arg2;
 } top2_t;
 
 static void top2_init(top2_t* t) {
   t->best = -INFINITY;
   t->second = -INFINITY;
   t->arg = -1;
+  t->arg2 = -1;
 }
 
 static void top2_push(top2_t* t, double s, int32_t v) {
   if (t->arg < 0 || s > t->best) {
     t->second = (t->arg < 0) ? -INFINITY : t->best;
+    t->arg2 = t->arg;
     t->best = s;
     t->arg = v;
-  } else if (s > t->second) {
+  } else if (t->arg2 < 0 || s > t->second) {
     t->second = s;
+    t->arg2 = v;
   }
+}
+
+static void top2_report(const top2_t* t, double* samp) {
+  samp[0] = t->best;
+  samp[1] = t->second;
+  samp[2] = t->best - t->second;
+  samp[4] = (double)t->arg2;
+}
+
+/* The arg-max bookkeeping on its own, over a given score vector (entries equal to -inf are not
+ * candidates): returns the winner's index and fills samp[0], [1], [2], [4] as the verification
+ * does.  Exposed so that the bookkeeping can be checked on vectors with exact ties, which the
+ * noise of the verification itself never produces. */
+int32_t ears_oracle_top2(const double* scores, int n, double* samp) {
+  top2_t t;
+  top2_init(&t);
+  for (int v = 0; v < n; ++v)
+    if (scores[v] > -INFINITY) top2_push(&t, scores[v], v);
+  top2_report(&t, samp);
+  return t.arg;
 }
 
 /* Shannon entropy of a probability vector in nats, -sum p log p over p > 0. */
@@ -250,9 +275,7 @@ int ears_oracle_verify_seq(const void* target_rows, const void* draft_rows, cons
   for (int i = 0; i < n; ++i) out_tokens[i] = tokens[i];
   out_tokens[n] = top.arg;
   if (samp) {
-    samp[0] = top.best;
-    samp[1] = top.second;
-    samp[2] = top.best - top.second;
+    top2_report(&top, samp);
     samp[3] = mode;
   }
   free(pt);

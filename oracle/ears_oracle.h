@@ -48,9 +48,10 @@ extern "C" {
 
 /* number of fp64 diagnostics stored per sequence for the sampled token:
  *   0 best score, 1 second-best score (over distinct vocabulary indices; -inf if none),
- *   2 gap = best - second, 3 mode (0 residual, 1 bonus, 2 residual empty -> target-row fallback)
+ *   2 gap = best - second, 3 mode (0 residual, 1 bonus, 2 residual empty -> target-row fallback),
+ *   4 vocabulary index of the second-best score (lowest index among equals; -1 if none)
  */
-#define EARS_ORACLE_NSAMP 4
+#define EARS_ORACLE_NSAMP 5
 
 /* uncertainty measure that scales the tolerance: the paper's 1 - max P_t (Section 3.2), the
  * normalised Shannon entropy H(P_t) / log V (the entropy of the distribution, which Section 5 names), or the
@@ -98,6 +99,11 @@ double ears_oracle_softmax(const void* row, int dtype, int V, double T, double* 
 double ears_oracle_entropy(const double* p, int V);
 /* Total variance sum_v p_v (1 - p_v) of the one-hot outcome drawn from p. */
 double ears_oracle_variance(const double* p, int V);
+
+/* Arg-max with lowest-index ties and its runner-up over scores[0..n) (-inf = not a candidate):
+ * returns the winner's index (-1 if there is no candidate) and fills samp[0] best score, [1]
+ * second-best score, [2] their gap, [4] the runner-up's index; samp[3] is left alone. */
+int32_t ears_oracle_top2(const double* scores, int n, double* samp);
 
 /* Verify one sequence.
  *   target_rows [K+1, V], draft_rows [K, V] row-major logits of type dtype

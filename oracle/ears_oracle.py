@@ -20,7 +20,7 @@ _LIB = os.path.join(_HERE, "libears_oracle.so")
 _LIB_OVERRIDE = os.environ.get("EARS_ORACLE_LIB")
 
 NDIAG = 10
-NSAMP = 4
+NSAMP = 5
 DIAG_NAMES = ("m_t", "Z_t", "P_t_x", "m_d", "Z_d", "P_d_x", "unc", "R", "U", "thr")
 
 _lib = None
@@ -70,6 +70,8 @@ def _load():
     lib.ears_oracle_entropy.restype = c.c_double
     lib.ears_oracle_variance.argtypes = [c.c_void_p, c.c_int]
     lib.ears_oracle_variance.restype = c.c_double
+    lib.ears_oracle_top2.argtypes = [c.c_void_p, c.c_int, c.c_void_p]
+    lib.ears_oracle_top2.restype = c.c_int32
     lib.ears_oracle_verify.argtypes = [
         c.c_void_p, c.c_void_p, c.c_void_p, c.c_int, c.c_int, c.c_int, c.c_int, c.c_double,
         c.c_double, c.c_int, c.c_uint64, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p,
@@ -144,13 +146,22 @@ def softmax(row: np.ndarray, T: float):
     return p, m.value, Z.value, float(pmax)
 
 
+def top2(scores: np.ndarray):
+    """Arg-max (lowest index on ties) and runner-up of a float64 score vector; -inf entries are not
+    candidates.  Returns (winner index, samp[NSAMP]) with samp[3] unused (nan)."""
+    scores = np.ascontiguousarray(scores, dtype=np.float64)
+    samp = np.full(NSAMP, np.nan)
+    arg = _load().ears_oracle_top2(_ptr(scores), scores.shape[0], _ptr(samp))
+    return int(arg), samp
+
+
 @dataclass
 class OracleResult:
     accept_len: np.ndarray  # [B] int32
     tokens: np.ndarray      # [B, K+1] int32 (ragged: packed like target rows)
     diag: np.ndarray        # [B, K, NDIAG] float64 (ragged: [rows, NDIAG])
     path: np.ndarray        # [B, K] int32 (ragged: [rows])
-    samp: np.ndarray        # [B, NSAMP] float64
+    samp: np.ndarray        # [B, NSAMP] float64: best, second, gap, mode, runner-up index
     status: int             # 1 if some draft token was out of range
 
     def d(self, name: str) -> np.ndarray:

@@ -3,7 +3,9 @@
 The bar: accept lengths and token indices bit-exact, except where the oracle itself says the
 decision is numerically undecidable: |R - threshold| < 1e-6 (or |R - U| < 1e-6 for the branch id)
 at the first position where the two decisions differ, or a Gumbel top-2 score gap below 1e-6 for
-the sampled token.  After an exempt decision difference the rest of that sequence is not compared.
+the sampled token, and then only when the differing token is the oracle's runner-up (the one other
+entry that is a valid outcome inside the band).  After an exempt decision difference the rest of
+that sequence is not compared.
 Softmax statistics: relative 1e-5 (fp32 logits) / 2e-3 (bf16 logits) on Z, p_t(x), p_d(x), R and
 max p = 1/Z, the row maximum exact, and absolute 1e-6 on the uncertainty and the threshold.
 """
@@ -123,9 +125,12 @@ def compare(ora, g_accept, g_tokens, g_stats, g_path, row_offsets, K, stats_rtol
         assert np.array_equal(g_tok[t0:t0 + n_o], o_tok[t0:t0 + n_o]), ("prefix", b)
         assert np.all(g_tok[t0 + n_o + 1:t0 + Kb + 1] == -1), ("tail", b)
         if g_tok[t0 + n_o] != o_tok[t0 + n_o]:
-            gap = ora.samp[b, 2]
+            gap, runner_up = ora.samp[b, 2], int(ora.samp[b, 4])
             assert gap < BAND, ("sampled token differs outside the band", b, n_o,
                                 int(g_tok[t0 + n_o]), int(o_tok[t0 + n_o]), float(gap))
+            assert int(g_tok[t0 + n_o]) == runner_up, (
+                "inside the band only the oracle's runner-up is a valid other outcome", b, n_o,
+                int(g_tok[t0 + n_o]), runner_up)
             rep.exempt_tokens += 1
             rep.notes.append(("token", b, n_o, float(gap)))
     return rep

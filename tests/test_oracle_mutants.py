@@ -40,8 +40,11 @@ MUTANTS = [
     ("bonus_row", "const void* row = row_ptr(target_rows, dtype, K, V);",
      "const void* row = row_ptr(target_rows, dtype, K - 1, V);", PINS[1:2]),
     ("bonus_ignores_temperature", "top2_push(&top, l / T + ears_oracle_gumbel", "top2_push(&top, l + ears_oracle_gumbel", PINS[1:2]),
-    # not planted: `s >= t->best` in the Gumbel arg-max (ties to the highest index).  Two entries tie
-    # only if their 40-bit noise values and residuals coincide; no input of feasible size shows it.
+    ("argmax_ties_to_highest_index", "if (t->arg < 0 || s > t->best) {", "if (t->arg < 0 || s >= t->best) {", PINS[1:2]),
+    ("runner_up_not_updated_by_new_winner", "    t->second = (t->arg < 0) ? -INFINITY : t->best;\n    t->arg2 = t->arg;\n", "", PINS[1:2]),
+    ("runner_up_index_stale", "    t->second = s;\n    t->arg2 = v;\n", "    t->second = s;\n", PINS[1:2]),
+    ("runner_up_ties_to_highest_index", "} else if (t->arg2 < 0 || s > t->second) {", "} else if (t->arg2 < 0 || s >= t->second) {", PINS[1:2]),
+    ("gap_of_winner_with_itself", "samp[2] = t->best - t->second;", "samp[2] = t->best - t->best;", PINS[1:2]),
     ("entropy_in_bits", "H -= p[v] * log(p[v]);", "H -= p[v] * log2(p[v]);", PINS[1:2]),
     ("variance_is_sum_of_squares", "G += p[v] * (1.0 - p[v]);", "G += p[v] * p[v];", PINS[1:2]),
     ("variance_measure_not_selected", "    if (unc_mode == EARS_ORACLE_UNC_VARIANCE) unc = ears_oracle_variance(pt, V);\n", "", PINS[1:2]),

@@ -429,6 +429,107 @@ def test_residual_law_and_empty_residual_fallback(oracle):
     assert stats.chisquare(np.delete(obs2, 3), np.delete(pt, 3) * rej2.sum()).pvalue > 1e-4
 
 
+# ------------------------------------------ the Gumbel arg-max, its runner-up and their gap
+LN2 = math.log(2.0)
+
+
+def _pow2_logits(exponents):
+    """fp32 logits k (small integers): at temperature 1/ln 2 their softmax weights are 2^k."""
+    return np.asarray(exponents, dtype=np.float32)
+
+
+def _numpy_top2(scores):
+    """(winner, runner-up) of a score vector by a stable sort: highest score first, lowest index
+    first among equals; -inf entries are not candidates."""
+    scores = np.asarray(scores, dtype=np.float64)
+    cand = [v for v in np.argsort(-scores, kind="stable") if scores[v] > -np.inf]
+    return (cand[0] if cand else -1), (cand[1] if len(cand) > 1 else -1)
+
+
+def test_top2_bookkeeping_against_sort(oracle):
+    # exact ties (which the verification's own noise never produces) and every ordering of three
+    # distinct values, against numpy's stable sort
+    cases = [[1.0, 2.0, 3.0], [3.0, 2.0, 1.0], [2.0, 3.0, 1.0], [1.0, 3.0, 2.0], [3.0, 1.0, 2.0],
+             [2.0, 1.0, 3.0],
+             [5.0, 5.0], [1.0, 5.0, 5.0], [5.0, 1.0, 5.0], [5.0, 5.0, 5.0], [7.0, 5.0, 5.0],
+             [5.0, 5.0, 7.0], [-np.inf, 4.0], [4.0], [-np.inf, -np.inf], [0.5, -np.inf, 0.5, 0.25]]
+    rng = np.random.default_rng(8)
+    cases += [list(rng.integers(0, 4, n).astype(np.float64)) for n in range(1, 9) for _ in range(20)]
+    for sc in cases:
+        arg, samp = oracle.top2(np.array(sc))
+        w, r = _numpy_top2(sc)
+        assert arg == w, sc
+        assert int(samp[4]) == r, sc
+        if w >= 0:
+            assert samp[0] == sc[w]
+        if r >= 0:
+            assert samp[1] == sc[r] and samp[2] == sc[w] - sc[r], sc
+        elif w >= 0:
+            assert samp[1] == -np.inf and samp[2] == np.inf, sc
+
+
+def test_replacement_scores_runner_up_and_gap(oracle):
+    # P_t = (1/2, 1/4, 1/8, 1/8), P_d = (1/8, 1/8, 1/4, 1/2) as exact powers of two (T = 1/ln 2),
+    # draft token 3: R = 1/4; the sequences picked have U >= 1/2, so with beta = 0 they reject.
+    # Residual max(0, P_t - P_d) = (3/8, 1/8, 0, 0): two candidates with scores
+    # log(3/8) + g(0) and log(1/8) + g(1), written out here with numpy.
+    T = 1.0 / LN2
+    lt, ld = _pow2_logits([-1, -2, -3, -3]), _pow2_logits([-3, -3, -2, -1])
+    target = np.stack([lt, lt])[None]
+    draft = ld[None, None]
+    tokens = np.array([[3]], dtype=np.int32)
+    seed = 2024
+    first_wins = 0
+    s = 0
+    for _ in range(60):
+        s = _find_seq(oracle, seed, 0, 0.5, 1.0, start=s + 1)
+        r = oracle.verify(target, draft, tokens, T, 0.0, seed, seq_ids=np.array([s]))
+        assert r.accept_len[0] == 0 and r.samp[0, 3] == 0.0
+        pt, pd = softmax64(lt, T), softmax64(ld, T)
+        q = pt - pd
+        sc = np.array([math.log(q[0]) + oracle.gumbel(seed, s, 0, 0),
+                       math.log(q[1]) + oracle.gumbel(seed, s, 0, 1)])
+        w = 0 if sc[0] >= sc[1] else 1
+        first_wins += (w == 0)
+        assert r.tokens[0, 0] == w
+        assert r.samp[0, 0] == pytest.approx(sc[w], abs=1e-12)
+        assert r.samp[0, 1] == pytest.approx(sc[1 - w], abs=1e-12)
+        assert r.samp[0, 2] == pytest.approx(sc[w] - sc[1 - w], abs=1e-12)
+        assert r.samp[0, 2] > 0.0
+        assert int(r.samp[0, 4]) == 1 - w
+    assert 30 <= first_wins < 60          # both orders of arrival were exercised (3:1 odds)
+
+
+def test_single_candidate_has_no_runner_up(oracle):
+    # P_t = (3/4, 1/4), P_d = (1/4, 3/4), draft token 1: R = 1/3; residual (1/2, 0): one candidate
+    T = 1.0
+    target = np.stack([logits_from_probs([0.75, 0.25], T)] * 2)[None]
+    draft = logits_from_probs([0.25, 0.75], T)[None, None]
+    s = _find_seq(oracle, 9, 0, 0.5, 1.0)
+    r = oracle.verify(target, draft, np.array([[1]], dtype=np.int32), T, 0.0, 9, seq_ids=np.array([s]))
+    assert r.accept_len[0] == 0 and r.tokens[0, 0] == 0
+    assert r.samp[0, 0] == pytest.approx(math.log(0.5) + oracle.gumbel(9, s, 0, 0), abs=1e-7)
+    assert r.samp[0, 1] == -np.inf and r.samp[0, 2] == np.inf and int(r.samp[0, 4]) == -1
+
+
+def test_bonus_scores_runner_up_and_gap(oracle):
+    # identical rows accept everything; the bonus token is arg-max of l/T + g over target row K
+    T = 0.7
+    l0 = np.array([0.5, -1.0, 2.0], dtype=np.float32)
+    lK = np.array([1.0, 0.25, -0.5], dtype=np.float32)
+    target = np.stack([l0, lK])[None]
+    draft = l0[None, None]
+    for s in range(40):
+        r = oracle.verify(target, draft, np.array([[1]], dtype=np.int32), T, 0.3, 5, seq_ids=np.array([s]))
+        assert r.accept_len[0] == 1 and r.samp[0, 3] == 1.0
+        sc = np.array([float(lK[v]) / T + oracle.gumbel(5, s, 1, v) for v in range(3)])
+        w, ru = _numpy_top2(sc)
+        assert r.tokens[0, 1] == w and int(r.samp[0, 4]) == ru
+        assert r.samp[0, 0] == pytest.approx(sc[w], abs=1e-12)
+        assert r.samp[0, 1] == pytest.approx(sc[ru], abs=1e-12)
+        assert r.samp[0, 2] == pytest.approx(sc[w] - sc[ru], abs=1e-12)
+
+
 # ----------------------------------------------- alternative uncertainty measure (Section 5)
 def test_residual_support_ignores_rounding_noise(oracle):
     """Target and draft put 1 - 3.5e-13 on entry 0 and differ only far down the tail, so that
