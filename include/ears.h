@@ -191,6 +191,32 @@ int ears_verify_ex(int dtype, const void* target_logits, const void* draft_logit
                    int32_t* out_path, uint32_t* status_word, void* stream);
 
 /* ---------------------------------------------------------------------------------------------
+ * ears_verify_ex for callers that must not allocate: code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc.  Same arguments and results as ears_verify_ex, without
+ * the workspace: the scratch is a fixed array of EARS_NOALLOC_SCRATCH_BYTES in device memory that
+ * is part of the library's code object (every GPU the library runs on holds its own copy until the
+ * process ends).  The call makes no hipMalloc / hipFree and calls no allocating routine.
+ *   - Problems whose ears_workspace_bytes(total_draft_rows, B, V) exceeds
+ *     EARS_NOALLOC_SCRATCH_BYTES are rejected with EARS_ERR_WORKSPACE (checked on the host, before
+ *     any HIP call, like every other argument).  4 MiB covers e.g. B = 1024 ragged sequences with
+ *     4608 draft rows, or B = 4096, K = 8.
+ *   - The first call on a device looks up the array's address (hipGetSymbolAddress; no
+ *     allocation); make that first call outside stream capture.
+ *   - All calls on one GPU share that GPU's array: calls that overlap in time on one GPU (two
+ *     streams, two threads) race, and a STATS stage's cached statistics last only until the next
+ *     call of this entry point on that GPU.  Nothing in the array needs clearing between calls.
+ * ------------------------------------------------------------------------------------------- */
+#define EARS_NOALLOC_SCRATCH_BYTES (4u << 20)
+
+int ears_verify_noalloc(int dtype, const void* target_logits, const void* draft_logits,
+                        const int32_t* draft_tokens, const int64_t* row_offsets,
+                        int64_t total_draft_rows, int B, int K, int V, float temperature, float beta,
+                        const float* temperature_per_seq, const float* beta_per_seq, int uncertainty,
+                        uint64_t seed, const int64_t* seq_ids, int stages, int32_t* out_accept_len,
+                        int32_t* out_tokens, double* out_stats, int32_t* out_path,
+                        uint32_t* status_word, void* stream);
+
+/* ---------------------------------------------------------------------------------------------
  * Temperature -> 0 (greedy decoding, the deterministic regime of the paper's Section 1).  In that
  * limit p_t and p_d are indicators of their rows' largest logits, R is 1 or 0, the uncertainty
  * and the tolerance vanish: a draft token is accepted iff it is the arg-max of its target row

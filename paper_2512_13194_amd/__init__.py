@@ -8,6 +8,7 @@
 from .binding import (  # noqa: F401
     EARS_BF16,
     EARS_F32,
+    EARS_NOALLOC_SCRATCH_BYTES,
     EARS_NSTATS,
     EARS_OK,
     EARS_STAGE_ALL,
@@ -31,6 +32,7 @@ from .binding import (  # noqa: F401
     ears_verify_ex,
     ears_verify_f32,
     ears_verify_greedy,
+    ears_verify_noalloc,
     ears_verify_ragged_bf16,
     ears_verify_ragged_f32,
     ears_workspace_bytes,

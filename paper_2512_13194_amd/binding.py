@@ -59,6 +59,9 @@ def lib() -> ctypes.CDLL:
         L.ears_verify_ex.argtypes = [i32, vp, vp, vp, vp, i64, i32, i32, i32, f32, f32, vp, vp, i32,
                                      u64, vp, vp, sz, i32, vp, vp, vp, vp, vp, vp]
         L.ears_verify_ex.restype = i32
+        L.ears_verify_noalloc.argtypes = [i32, vp, vp, vp, vp, i64, i32, i32, i32, f32, f32, vp, vp,
+                                          i32, u64, vp, i32, vp, vp, vp, vp, vp, vp]
+        L.ears_verify_noalloc.restype = i32
         L.ears_greedy_workspace_bytes.argtypes = [i64, i32]
         L.ears_greedy_workspace_bytes.restype = sz
         L.ears_verify_greedy.argtypes = [i32, vp, vp, vp, i64, i32, i32, i32, vp, sz, vp, vp, vp]
@@ -228,6 +231,34 @@ def ears_verify_ex(target_logits, draft_logits, draft_tokens, *, row_offsets=Non
         _ptr(status_word), _stream(stream)))
     return dict(accept_len=out_accept_len, tokens=out_tokens, stats=stats, path=path,
                 workspace=workspace)
+
+
+EARS_NOALLOC_SCRATCH_BYTES = 4 << 20
+
+
+def ears_verify_noalloc(target_logits, draft_logits, draft_tokens, out_accept_len, out_tokens, *,
+                        row_offsets=None, temperature=1.0, beta=0.0, temperature_per_seq=None,
+                        beta_per_seq=None, uncertainty=EARS_UNCERTAINTY_MAXPROB, seed=0, seq_ids=None,
+                        stages=EARS_STAGE_ALL, out_stats=None, out_path=None, status_word=None,
+                        stream=None):
+    """ears_verify_ex on the library's fixed device scratch: allocates nothing, here or in the
+    library, so every output tensor is the caller's (accept_len [B], tokens [R + B] int32)."""
+    V = target_logits.shape[-1]
+    if row_offsets is None:
+        B, K1, _ = target_logits.shape
+        K = K1 - 1
+        R = B * K
+    else:
+        B = row_offsets.shape[0] - 1
+        R = draft_logits.shape[0]
+        K = 0
+    _check(lib().ears_verify_noalloc(
+        _dtype_code(target_logits), _ptr(target_logits), _ptr(draft_logits), _ptr(draft_tokens),
+        _ptr(row_offsets), R, B, K, V, float(temperature), float(beta), _ptr(temperature_per_seq),
+        _ptr(beta_per_seq), int(uncertainty), int(seed), _ptr(seq_ids), int(stages),
+        _ptr(out_accept_len), _ptr(out_tokens), _ptr(out_stats), _ptr(out_path), _ptr(status_word),
+        _stream(stream)))
+    return out_accept_len, out_tokens
 
 
 def ears_greedy_workspace_bytes(total_draft_rows: int, B: int) -> int:

@@ -195,6 +195,27 @@ static int scratch_get(size_t bytes, void** out) {
   return EARS_OK;
 }
 
+// Scratch of ears_verify_noalloc: a fixed array in device memory that comes with the code object,
+// one copy per device the library runs on, each at its own address.  In host code the array's
+// name is only a handle for hipGetSymbolAddress; kernels get the resolved address as an argument.
+static __device__ __align__(256) unsigned char scratch[EARS_NOALLOC_SCRATCH_BYTES];
+static std::mutex g_static_mutex;
+static void* g_static_ptr[kMaxDevices] = {};
+
+static int static_scratch_get(void** out) {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return EARS_ERR_HIP;
+  std::lock_guard<std::mutex> lock(g_static_mutex);
+  if (!g_static_ptr[dev]) {
+    void* ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || ptr == nullptr)
+      return EARS_ERR_HIP;
+    g_static_ptr[dev] = ptr;
+  }
+  *out = g_static_ptr[dev];
+  return EARS_OK;
+}
+
 }  // namespace ears
 
 using namespace ears;
@@ -271,6 +292,37 @@ int ears_verify_ex(int dtype, const void* target_logits, const void* draft_logit
   p.status_word = status_word;
   hipStream_t s = static_cast<hipStream_t>(stream);
   return dtype == EARS_F32 ? launch<F32>(p, stages, s) : launch<BF16>(p, stages, s);
+}
+
+int ears_verify_noalloc(int dtype, const void* target_logits, const void* draft_logits,
+                        const int32_t* draft_tokens, const int64_t* row_offsets,
+                        int64_t total_draft_rows, int B, int K, int V, float temperature, float beta,
+                        const float* temperature_per_seq, const float* beta_per_seq, int uncertainty,
+                        uint64_t seed, const int64_t* seq_ids, int stages, int32_t* out_accept_len,
+                        int32_t* out_tokens, double* out_stats, int32_t* out_path,
+                        uint32_t* status_word, void* stream) {
+  // every argument check, and the size limit, before the first HIP call
+  WorkspaceLayout lay;
+  alignas(256) static char dummy[256];
+  int rc = validate(dtype, target_logits, draft_logits, draft_tokens, row_offsets, total_draft_rows,
+                    B, K, V, temperature, beta, temperature_per_seq, beta_per_seq, seq_ids, dummy,
+                    (size_t)-1, stages, out_accept_len, out_tokens, out_stats, out_path, status_word,
+                    &lay);
+  if (rc != EARS_OK) return rc;
+  if (uncertainty != EARS_UNCERTAINTY_MAXPROB && uncertainty != EARS_UNCERTAINTY_ENTROPY &&
+      uncertainty != EARS_UNCERTAINTY_VARIANCE)
+    return EARS_ERR_PARAM;
+  if (lay.total > (size_t)EARS_NOALLOC_SCRATCH_BYTES) return EARS_ERR_WORKSPACE;
+  void* ws = nullptr;
+  rc = static_scratch_get(&ws);
+  if (rc != EARS_OK) return rc;
+  // Nothing in the scratch has to start at zero: every word a stage reads was written earlier in
+  // the same call (or by the stage that cached the statistics), so the last call's contents are
+  // simply overwritten.
+  return ears_verify_ex(dtype, target_logits, draft_logits, draft_tokens, row_offsets,
+                        total_draft_rows, B, K, V, temperature, beta, temperature_per_seq,
+                        beta_per_seq, uncertainty, seed, seq_ids, ws, EARS_NOALLOC_SCRATCH_BYTES,
+                        stages, out_accept_len, out_tokens, out_stats, out_path, status_word, stream);
 }
 
 static int verify_simple(int dtype, const void* target, const void* draft, const int32_t* tokens,

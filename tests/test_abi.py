@@ -105,6 +105,28 @@ def test_ex_argument_errors(L):
     assert _ex(L, wsb=need - 1) == b.EARS_ERR_WORKSPACE
 
 
+def test_noalloc_argument_errors(L):
+    """Every check of the entry point without a workspace, its size limit included, happens on the
+    host before the first HIP call."""
+    from paper_2512_13194_amd import binding as b
+
+    def call(dtype=1, target=P, draft=P, tokens=P, off=None, R=6, B=2, K=3, V=64, T=1.0, beta=0.1,
+             unc=0, stages=7, acc=P, out=P):
+        return L.ears_verify_noalloc(dtype, target, draft, tokens, off, R, B, K, V, T, beta, None, None,
+                                     unc, 0, None, stages, acc, out, None, None, None, None)
+    assert call(dtype=5) == b.EARS_ERR_DTYPE
+    assert call(target=None) == b.EARS_ERR_NULL
+    assert call(acc=None) == b.EARS_ERR_NULL
+    assert call(R=7) == b.EARS_ERR_SHAPE
+    assert call(T=-1.0) == b.EARS_ERR_PARAM
+    assert call(unc=9) == b.EARS_ERR_PARAM
+    assert call(stages=0) == b.EARS_ERR_PARAM
+    assert call(draft=P + 8) == b.EARS_ERR_ALIGN
+    # statistics of 4096 * 64 positions do not fit the fixed scratch
+    assert b.ears_workspace_bytes(4096 * 64, 4096, 8) > b.EARS_NOALLOC_SCRATCH_BYTES
+    assert call(R=4096 * 64, B=4096, K=64, V=8) == b.EARS_ERR_WORKSPACE
+
+
 def test_ragged_argument_errors(L):
     from paper_2512_13194_amd import binding as b
     f = L.ears_verify_ragged_bf16
