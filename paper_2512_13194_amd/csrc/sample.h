@@ -29,6 +29,8 @@
 // a row is split into at most two chunks (sample_select_kernel: filter and select in one).
 #pragma once
 
+#include <type_traits>
+
 #include "decide.h"
 #include "ears_device.h"
 
@@ -159,6 +161,23 @@ __device__ Best exact_scan(const SampleCtx& c, int v0, int v1, int mode, Best be
   return best;
 }
 
+// A load whose address is the same in every lane, from memory that no kernel writes while this one
+// runs: through the constant address space it is a scalar load.
+template <typename T>
+__device__ __forceinline__ T uniform_load(const T* ptr) {
+  typedef const T __attribute__((address_space(4))) * const_ptr;
+  return *(const_ptr)(uintptr_t)ptr;
+}
+
+// Integers ordered like the floats they stand for (finite values), and back.
+__device__ __forceinline__ int ordered_int(float x) {
+  const int b = __float_as_int(x);
+  return b ^ ((b >> 31) & 0x7FFFFFFF);
+}
+__device__ __forceinline__ float ordered_float(int k) {
+  return __int_as_float(k ^ ((k >> 31) & 0x7FFFFFFF));
+}
+
 __device__ __forceinline__ int lanes_below(unsigned long long mask) {
   return (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32),
                                         __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
@@ -166,11 +185,24 @@ __device__ __forceinline__ int lanes_below(unsigned long long mask) {
 
 // The filter of chunk s = blockIdx.x * G + g of sequence blockIdx.y, by sub-block g (512 threads)
 // of a workgroup of G * 512 threads.  With G > 1 a workgroup filters G chunks of one row side by
-// side; the sub-blocks share nothing but the accept length and the barriers.
+// side; the sub-blocks share the accept length, the thresholds their waves publish, and the
+// barriers.  Returns true when the workgroup has settled the row's token by itself (kFused: the
+// chunks of this workgroup are the whole row, exactly one entry survived and it has been written).
 // kLate: the decisions are taken here, from the cached statistics (a DECIDE | SAMPLE call); kept
 // out of the other instantiations because the fp64 decision raises the register count.
-template <typename DT, int G, bool kLate>
-__device__ __forceinline__ void sample_body(const Problem& p) {
+//
+// Per tile a lane owns kSampleLaneElems consecutive entries and one coarse Philox block.  The
+// common path never looks at an entry on its own:
+//   - entries whose coarse byte is 255 (N = 0: the level-1 bound is vacuous) are found with three
+//     bit operations per noise word and queued for level 2;
+//   - all other entries have N >= 1, so none of the lane's entries can pass level 1 unless the
+//     lane's largest logit passes it with N = 1; a lane for which it does is queued as a whole
+//     ("group") and its 16 entries are tested one by one later, 64 groups at a time, against the
+//     threshold of that later moment.
+// Waves publish their thresholds in LDS and pick up the largest at every tile: a lower bound of
+// the best score of any part of the row is one of the whole row's best score.
+template <typename DT, int G, bool kLate, bool kFused>
+__device__ __forceinline__ bool sample_body(const Problem& p) {
   constexpr int kPer = DT::kPerVec;
   constexpr int kVecs = kSampleLaneElems / kPer;  // 16-byte loads per lane and tile
   constexpr int kTile = kSampleTileElems;
@@ -178,36 +210,55 @@ __device__ __forceinline__ void sample_body(const Problem& p) {
   using storage = typename DT::storage;
 
   constexpr int kWaves = G * kWavesPerBlock;               // waves of the whole workgroup
-  __shared__ int sh_queue[kWaves][kQueueCap];              // queued vocabulary indices ...
-  __shared__ int sh_queue_h[kWaves][kQueueCap];            // ... and their coarse noise bytes
+  // Entries queued for level 2 (vocabulary index and coarse noise byte) and groups queued for the
+  // entry-by-entry level 1 (index of their first entry): kQueueCap slots per wave, then a pool that
+  // all waves of the workgroup fill and empty together (each contributes fewer than 64).
+  constexpr int kPool = kWaves * kQueueCap, kPoolCap = kWaves * kWave;
+  __shared__ int sh_ent_v[kPool + kPoolCap];
+  __shared__ int sh_ent_h[kPool + kPoolCap];
+  __shared__ int sh_grp[kPool + kPoolCap];
+  __shared__ int sh_pool_n[3];                             // warm-up entries, last groups, last entries
   __shared__ int sh_surv_v[kWaves][kSurvivorCap];
   __shared__ float sh_surv_s[kWaves][kSurvivorCap];
-  __shared__ float sh_theta[kWaves];
-  __shared__ int sh_n, sh_count_g[G], sh_overflow_g[G];
+  __shared__ int sh_theta_row;                             // the row's threshold, as an ordered integer
+  __shared__ int sh_n, sh_count_g[G], sh_overflow_g[G], sh_only;
 
-  const int g = (int)threadIdx.x / kBlock;                 // sub-block, uniform over a wave
-  const int tid = (int)threadIdx.x - g * kBlock, lane = tid & (kWave - 1);
-  const int wave = (int)threadIdx.x / kWave;               // index into the per-wave arrays
-  const int wave_g = tid / kWave;                          // wave within the sub-block
+  // wave-uniform quantities are kept in scalar registers: the branches on them are scalar branches
+  const int wave = __builtin_amdgcn_readfirstlane((int)threadIdx.x / kWave);  // within the workgroup
+  const int g = wave / kWavesPerBlock;                     // sub-block
+  const int wave_g = wave - g * kWavesPerBlock;            // wave within the sub-block
+  const int tid = (int)threadIdx.x - g * kBlock, lane = (int)threadIdx.x & (kWave - 1);
   const int s = (int)blockIdx.x * G + g, b = (int)blockIdx.y;
   const int V = p.V;
 
   // ---- accept length of this sequence ---------------------------------------------------------
   const int Kb = seq_len(p, b);
   if (tid == 0) { sh_count_g[g] = 0; sh_overflow_g[g] = 0; }
-  if (p.decide_fused) {
-    // one decision per position, left by the statistics kernel or taken here from the cached
-    // statistics; the first rejection is the accept length
-    if (wave == 0) {
-      const int nn = first_reject_scan(p, b, lane, !kLate, s == 0);
-      if (lane == 0) sh_n = nn;
+  if (threadIdx.x == 0) sh_only = -1;
+  if (threadIdx.x == 0) sh_theta_row = ordered_int(kNoThreshold);
+  if (threadIdx.x < 3) sh_pool_n[threadIdx.x] = 0;
+  int n;
+  if (!kLate && p.decide_fused) {
+    // one decision per position, left by the statistics kernel: every wave scans them for itself
+    // (the same few words for all of them), the first wave of the row's first chunk stores the
+    // accept length and the accepted prefix
+    n = first_reject_scan(p, b, lane, true, s == 0 && wave_g == 0);
+    __syncthreads();  // thresholds initialised before any wave reads another's
+  } else {
+    if (kLate) {
+      // the decisions are taken here from the cached statistics, by one wave
+      if (wave == 0) {
+        const int nn = first_reject_scan(p, b, lane, false, s == 0);
+        if (lane == 0) sh_n = nn;
+      }
+    } else if (threadIdx.x == 0) {
+      const int nn = p.accept_len[b];
+      sh_n = nn < 0 ? 0 : (nn > Kb ? Kb : nn);
     }
-  } else if (threadIdx.x == 0) {
-    const int nn = p.accept_len[b];
-    sh_n = nn < 0 ? 0 : (nn > Kb ? Kb : nn);
+    __syncthreads();
+    n = sh_n;
   }
-  __syncthreads();
-  const int n = sh_n;
+  n = __builtin_amdgcn_readfirstlane(n);
 
   const int64_t r0 = seq_row_begin(p, b);
   const bool residual = n < Kb;
@@ -218,14 +269,43 @@ __device__ __forceinline__ void sample_body(const Problem& p) {
   const uint64_t seed = p.seed, seq = seq_rng_id(p, b);
   const uint32_t pos = (uint32_t)n;
 
-  // fp32 constants of levels 1 and 2
+  const int v_begin = s * p.chunk;
+  const int v_end = (V - v_begin) < p.chunk ? V : v_begin + p.chunk;
+  const bool vector_ok = (reinterpret_cast<uintptr_t>(trow) & 15u) == 0;
+
+  // One 16-byte load; rows that are not 16-byte aligned (or the ragged last vector) are assembled
+  // from element loads into the same packed form, padded with -inf.  Ordinary cached loads: a
+  // lane's loads of one tile are adjacent 16-byte pieces of the same cache lines, which
+  // non-temporal loads would fetch from memory once per piece (1.6x the row's bytes, measured).
+  auto load_raw = [&](int vb, int v_end) -> uint4 {
+    if (vb >= v_end) return DT::neg_inf_vec();
+    if (vector_ok && vb + kPer <= v_end) return *reinterpret_cast<const uint4*>(trow + vb);
+    uint32_t wds[4];
+#pragma unroll
+    for (int d = 0; d < 4; ++d) {
+      if (sizeof(storage) == 2) {
+        const uint32_t lo = (vb + 2 * d < v_end) ? (uint32_t)reinterpret_cast<const uint16_t*>(trow)[vb + 2 * d] : 0xFF80u;
+        const uint32_t hi = (vb + 2 * d + 1 < v_end) ? (uint32_t)reinterpret_cast<const uint16_t*>(trow)[vb + 2 * d + 1] : 0xFF80u;
+        wds[d] = lo | (hi << 16);
+      } else {
+        wds[d] = (vb + d < v_end) ? reinterpret_cast<const uint32_t*>(trow)[vb + d] : 0xFF800000u;
+      }
+    }
+    return make_uint4(wds[0], wds[1], wds[2], wds[3]);
+  };
+
+  const int lane_off = tid * kSampleLaneElems;
+
+  // fp32 constants of levels 1 and 2.  The cached statistics are the same words for every lane:
+  // read through the constant address space they are scalar loads, which leave the vector-memory
+  // counter to the tile loads that follow.
   const float c = (float)(kLog2e / (double)Tf);
   float mt = 0.0f, kt = 0.0f, md = 0.0f, kd = 0.0f;
   if (residual) {
-    mt = p.m[2 * r];
-    md = p.m[2 * r + 1];
-    kt = -__builtin_amdgcn_logf((float)p.Z[2 * r]);
-    kd = -__builtin_amdgcn_logf((float)p.Z[2 * r + 1]);
+    mt = uniform_load(p.m + 2 * r);
+    md = uniform_load(p.m + 2 * r + 1);
+    kt = -__builtin_amdgcn_logf((float)uniform_load(p.Z + 2 * r));
+    kd = -__builtin_amdgcn_logf((float)uniform_load(p.Z + 2 * r + 1));
   }
   // level-1 bound, scaled by 2^23: l*cs + ks - bits(float(N)) >= theta * 2^23
   const float cs = c * 0x1p23f;
@@ -233,23 +313,17 @@ __device__ __forceinline__ void sample_body(const Problem& p) {
 
   float theta = kNoThreshold;  // wave-uniform: best proven lower bound of the maximum score (log2)
   int qcount = 0;            // wave-uniform: queued candidates
+  int gcount = 0;            // wave-uniform: queued groups
   int scount = 0;            // wave-uniform: survivors of this wave
   bool overflow = false;
 
-  // Level 2 for up to 64 queued elements, one per lane.  h_known is the element's coarse noise
-  // byte when the caller has it (queued elements), -1 when it has to be generated here.
-  auto evaluate = [&](int v, int h_known, bool active, float& s_up, float& s_lo) {
+  // Level 2 for up to 64 queued elements, one per lane; h is the element's coarse noise byte.
+  auto evaluate = [&](int v, uint32_t h, bool active, float& s_up, float& s_lo) {
     s_up = -INFINITY;
     s_lo = -INFINITY;
     const int vv = active ? v : 0;
     const float lt = DT::load(trow, vv);
     // u = (h + (f + 1/2) 2^-32) / 256 and 1 - u, each to fp32 relative accuracy
-    uint32_t h = (uint32_t)h_known;
-    if (h_known < 0) {
-      const uint32_t cw = philox_pick(noise_block(seed, seq, pos, kDomainCoarse, (uint32_t)vv >> 4),
-                                      (uint32_t)vv >> 2);
-      h = (cw >> (8u * ((uint32_t)vv & 3u))) & 0xFFu;
-    }
     const uint32_t f = philox_pick(noise_block(seed, seq, pos, kDomainFine, (uint32_t)vv >> 2),
                                    (uint32_t)vv);
     const float u = ((float)h + fmaf((float)f, 0x1p-32f, 0x1p-33f)) * 0x1p-8f;
@@ -302,15 +376,30 @@ __device__ __forceinline__ void sample_body(const Problem& p) {
     __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
   };
 
-  auto evaluate_batch = [&](int cnt) {
+  // The row's threshold: every wave of the workgroup filters the same row, so a lower bound of the
+  // best score of one wave's entries is one of the whole row's.  Kept in LDS as an integer whose
+  // order is the floats' (atomic maximum); a wave adopts it at every tile.
+  auto publish_threshold = [&]() {
+    if (lane == 0) atomicMax(&sh_theta_row, ordered_int(theta));
+  };
+  auto adopt_threshold = [&]() {
+    theta = fmaxf(theta, ordered_float(__hip_atomic_load(&sh_theta_row, __ATOMIC_RELAXED,
+                                                         __HIP_MEMORY_SCOPE_WORKGROUP)));
+  };
+
+  // level 2 for the cnt (at most 64) entries that start at slot `base` of the entry arrays
+  auto evaluate_batch = [&](int base, int cnt) {
     const bool active = lane < cnt;
     __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
-    const int v = active ? sh_queue[wave][qcount - cnt + lane] : 0;
-    const int h = active ? sh_queue_h[wave][qcount - cnt + lane] : 0;
-    qcount -= cnt;
+    const int v = active ? sh_ent_v[base + lane] : 0;
+    const int h = active ? sh_ent_h[base + lane] : 0;
     float s_up, s_lo;
-    evaluate(v, h, active, s_up, s_lo);
-    theta = fmaxf(theta, wave_max(s_lo));
+    evaluate(v, (uint32_t)h, active, s_up, s_lo);
+    const float best_lo = wave_max(s_lo);
+    if (best_lo > theta) {
+      theta = best_lo;
+      publish_threshold();
+    }
     const bool surv = active && s_up > -INFINITY && s_up >= theta;
     const unsigned long long sm = __ballot(surv);
     const int add = __popcll(sm);
@@ -325,102 +414,244 @@ __device__ __forceinline__ void sample_body(const Problem& p) {
     scount += add;
     __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
   };
+  const int q0 = wave * kQueueCap;  // this wave's slots of the entry and group arrays
 
-  const int v_begin = s * p.chunk;
-  const int v_end = (V - v_begin) < p.chunk ? V : v_begin + p.chunk;
-  const bool vector_ok = (reinterpret_cast<uintptr_t>(trow) & 15u) == 0;
+  // Entries waiting to be queued for level 2: bit 8 t + k of pend_pm stands for entry 4 k + t of the
+  // group that starts at pend_vb, whose coarse byte is byte t of noise word pend_w[k].
+  uint32_t pend_pm = 0u, pend_w0 = 0u, pend_w1 = 0u, pend_w2 = 0u, pend_w3 = 0u;
+  int pend_vb = 0;
 
-  // One 16-byte load; rows that are not 16-byte aligned (or the ragged last vector) are assembled
-  // from element loads into the same packed form, padded with -inf.  Ordinary cached loads: a
-  // lane's loads of one tile are adjacent 16-byte pieces of the same cache lines, which
-  // non-temporal loads would fetch from memory once per piece (1.6x the row's bytes, measured).
-  auto load_raw = [&](int vb) -> uint4 {
-    if (vb >= v_end) return DT::neg_inf_vec();
-    if (vector_ok && vb + kPer <= v_end) return *reinterpret_cast<const uint4*>(trow + vb);
-    uint32_t wds[4];
-#pragma unroll
-    for (int d = 0; d < 4; ++d) {
-      if (sizeof(storage) == 2) {
-        const uint32_t lo = (vb + 2 * d < v_end) ? (uint32_t)reinterpret_cast<const uint16_t*>(trow)[vb + 2 * d] : 0xFF80u;
-        const uint32_t hi = (vb + 2 * d + 1 < v_end) ? (uint32_t)reinterpret_cast<const uint16_t*>(trow)[vb + 2 * d + 1] : 0xFF80u;
-        wds[d] = lo | (hi << 16);
-      } else {
-        wds[d] = (vb + d < v_end) ? reinterpret_cast<const uint32_t*>(trow)[vb + d] : 0xFF800000u;
-      }
+  // One round: every lane with a waiting entry queues one (as a rule one round empties them all).
+  auto queue_round = [&]() {
+    const bool has = pend_pm != 0u;
+    const int q = has ? __builtin_ctz(pend_pm) : 0;
+    pend_pm &= pend_pm - 1u;
+    const int k = q & 7, t = q >> 3;
+    const int v = pend_vb + 4 * k + t;
+    const bool ok = has && v < V;  // beyond the row's end: padding of the last tile
+    const unsigned long long bal = __ballot(ok);
+    if (ok) {
+      // noise word k by bitwise selection (an indexed table of the four words would live in memory)
+      const uint32_t k0 = 0u - (uint32_t)(k & 1), k1 = 0u - (uint32_t)((k >> 1) & 1);
+      const uint32_t w_lo = (pend_w1 & k0) | (pend_w0 & ~k0), w_hi = (pend_w3 & k0) | (pend_w2 & ~k0);
+      const uint32_t wk = (w_hi & k1) | (w_lo & ~k1);
+      const int slot = q0 + qcount + lanes_below(bal);
+      sh_ent_v[slot] = v;
+      sh_ent_h[slot] = (int)((wk >> (8 * t)) & 0xFFu);
     }
-    return make_uint4(wds[0], wds[1], wds[2], wds[3]);
+    qcount += __popcll(bal);
   };
 
-  // a lane owns kSampleLaneElems consecutive entries of each tile: kVecs 16-byte loads and
-  // exactly one coarse Philox block
-  uint4 raw[kVecs];
-#pragma unroll
-  for (int k = 0; k < kVecs; ++k) raw[k] = load_raw(v_begin + tid * kSampleLaneElems + k * kPer);
-
-  // warm start: a first threshold from 64 elements of this wave's part of the chunk (their loads
-  // travel together with the first tile's)
-  {
-    const int v = v_begin + wave_g * kWave + lane;
-    float s_up, s_lo;
-    evaluate(v, -1, v < v_end, s_up, s_lo);
-    theta = fmaxf(theta, wave_max(s_lo));
-  }
-
-  for (int tile0 = v_begin; tile0 < v_end; tile0 += kTile) {
-    const int vbase = tile0 + tid * kSampleLaneElems;
+  // Level 1 entry by entry for the cnt (at most 64) groups that start at slot `base` of the group
+  // array, one group per lane: its entries and its coarse block are fetched again (the lines are
+  // still in the caches), and every entry with N >= 1 whose bound reaches the threshold of this
+  // moment is left waiting for the level-2 queue.
+  auto inspect_groups = [&](int base, int cnt) {
+    const bool active = lane < cnt;
+    __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+    // (a pooled group may belong to another chunk of the row than this wave's: the row's end bounds it)
+    const int vb = active ? sh_grp[base + lane] : V;
+    const float Theta = theta * 0x1p23f;
     float l[kSampleLaneElems];
 #pragma unroll
     for (int k = 0; k < kVecs; ++k) {
-      float g[kPer];
-      DT::unpack(raw[k], g);
+      float e[kPer];
+      DT::unpack(load_raw(vb + k * kPer, V), e);
 #pragma unroll
-      for (int j = 0; j < kPer; ++j) l[k * kPer + j] = g[j];
-      raw[k] = load_raw(vbase + kTile + k * kPer);  // next tile, in flight while this one is tested
+      for (int j = 0; j < kPer; ++j) l[k * kPer + j] = e[j];
     }
-    // level 1
-    const float Theta = theta * 0x1p23f;
-    const Philox coarse = noise_block(seed, seq, pos, kDomainCoarse, (uint32_t)vbase >> 4);
-    float bound[kSampleLaneElems];
-    uint32_t nw[4];
-    float bmax = -INFINITY;
+    const Philox coarse = noise_block(seed, seq, pos, kDomainCoarse, (uint32_t)(active ? vb : 0) >> 4);
+    uint32_t pm = 0u;
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
-      nw[k] = ~coarse.word(k);  // bytes N = 255 - h
+      const uint32_t nw = ~coarse.word(k);  // bytes N = 255 - h
 #pragma unroll
       for (int t = 0; t < 4; ++t) {
-        const int j = 4 * k + t;
-        const float Nf = (float)((nw[k] >> (8 * t)) & 0xFFu);
+        const float Nf = (float)((nw >> (8 * t)) & 0xFFu);
         // the bit pattern of float(N), read as an integer, is (log2 N + 127) * 2^23 from below
-        bound[j] = fmaf(l[j], cs, ks) - (float)__float_as_int(Nf);
-        bmax = fmaxf(bmax, bound[j]);
+        const float bound = fmaf(l[4 * k + t], cs, ks) - (float)__float_as_int(Nf);
+        // entries with N = 0 went to level 2 when their tile was filtered
+        if (bound >= Theta && Nf > 0.0f) pm |= 1u << (8 * t + k);
       }
     }
-    if (__ballot(bmax >= Theta) != 0ull) {
+    pend_pm = active ? pm : 0u;
+    pend_vb = vb;
+    pend_w0 = coarse.w0; pend_w1 = coarse.w1; pend_w2 = coarse.w2; pend_w3 = coarse.w3;
+  };
+
+  // Second half: the lane's entries other than those just left waiting have N >= 1, so none of them
+  // passes level 1 unless the largest logit does with N = 1 (bits(1.0f) = 127 * 2^23); a lane for
+  // which it does is queued as a group.
+  auto tile_groups = [&](float lmax, int tile0) {
+    const bool whole_group = fmaf(lmax, cs, ks) - 1065353216.0f >= theta * 0x1p23f;
+    const unsigned long long gb = __ballot(whole_group);
+    if (gb != 0ull) {
+      if (whole_group) sh_grp[q0 + gcount + lanes_below(gb)] = tile0 + lane_off;
+      gcount += __popcll(gb);
+    }
+  };
+
+  // Empties what a step left waiting: rounds of queueing; level 2 whenever a full batch is queued;
+  // level 1 entry by entry whenever 64 groups are queued.  Leaves fewer than 64 entries and at most
+  // 64 groups.
+  auto settle = [&]() {
+    for (;;) {
+      const bool waiting = __ballot(pend_pm != 0u) != 0ull;
+      if (waiting) queue_round();
+      if (qcount >= kWave) {
+        qcount -= kWave;
+        evaluate_batch(q0 + qcount, kWave);
+      }
+      if (waiting) continue;
+      if (gcount < kWave) break;
+      adopt_threshold();
+      // without any threshold every entry would pass: wait for one (another wave's, as a rule) as
+      // long as the next tile's groups still fit
+      if (theta <= kNoThreshold && gcount <= kQueueCap - kWave) break;
+      gcount -= kWave;
+      inspect_groups(q0 + gcount, kWave);
+    }
+  };
+
+  // All waves of the workgroup move what they have queued (fewer than 64 entries each) to the pool
+  // and share the level-2 work, 64 entries at a time, lanes fully used.  `which` names the pool's
+  // counter (each is used once).  Ends with the threshold of all of it adopted.
+  auto pool_evaluate = [&](int which) {
+    int base = 0;
+    if (lane == 0 && qcount > 0) base = atomicAdd(&sh_pool_n[which], qcount);
+    base = __builtin_amdgcn_readfirstlane(base);
+    if (lane < qcount) {
+      sh_ent_v[kPool + base + lane] = sh_ent_v[q0 + lane];
+      sh_ent_h[kPool + base + lane] = sh_ent_h[q0 + lane];
+    }
+    qcount = 0;
+    __syncthreads();
+    const int total = sh_pool_n[which];
+    adopt_threshold();
+    for (int b0 = wave * kWave; b0 < total; b0 += kWaves * kWave)
+      evaluate_batch(kPool + b0, total - b0 < kWave ? total - b0 : kWave);
+    __syncthreads();
+    adopt_threshold();
+  };
+
+  // ---- the tiles of this chunk --------------------------------------------------------------------
+  // kFast: rows that start on a 16-byte boundary and hold whole 16-byte vectors.  Their tile loads
+  // are unconditional vector loads (addresses clamped to the chunk, what lies beyond its end is
+  // masked after the load), so that the loads of the tiles ahead stay in flight while a tile is
+  // worked on: the count of outstanding loads is then known at every point of the loop.  Other rows
+  // are assembled from element loads.
+  auto stream = [&](auto fast_tag) {
+    constexpr bool kFast = decltype(fast_tag)::value;
+    const int last_vec = v_end - kPer;
+    auto load_tile = [&](uint4 (&raw)[kVecs], int tile_begin) {
 #pragma unroll
-      for (int j = 0; j < kSampleLaneElems; ++j) {
-        const bool pj = bound[j] >= Theta;
-        const unsigned long long bal = __ballot(pj);
-        if (bal != 0ull) {
-          if (pj) {
-            const int slot = qcount + lanes_below(bal);
-            sh_queue[wave][slot] = vbase + j;
-            sh_queue_h[wave][slot] = (int)(255u - ((nw[j >> 2] >> (8 * (j & 3))) & 0xFFu));
-          }
-          qcount += __popcll(bal);
-          if (qcount >= kWave) evaluate_batch(kWave);
+      for (int k = 0; k < kVecs; ++k) {
+        const int vb = tile_begin + lane_off + k * kPer;
+        if (kFast) raw[k] = *reinterpret_cast<const uint4*>(trow + (vb < last_vec ? vb : last_vec));
+        else raw[k] = load_raw(vb, v_end);
+      }
+    };
+    // kDepth tiles are in flight per lane (eight 16-byte loads), requested before anything else
+    // that depends on n.  The buffers are named apart and taken in turn: a copy from one to the
+    // next would wait for the load it copies.
+    constexpr int kDepth = 8 / kVecs;
+    static_assert(kDepth == 4 || kDepth == 2, "tile buffers");
+    uint4 raw0[kVecs], raw1[kVecs], raw2[kVecs], raw3[kVecs];
+    load_tile(raw0, v_begin);
+
+    // One tile, first half: `raw` holds this lane's entries of the tile that starts at tile0 and is
+    // refilled with those of the tile kDepth further on.  Leaves the entries with coarse byte 255
+    // waiting for the level-2 queue and returns the lane's largest logit.
+    auto tile_noise = [&](uint4 (&raw)[kVecs], int tile0, bool first) -> float {
+      const int vbase = tile0 + lane_off;
+      const Philox coarse = noise_block(seed, seq, pos, kDomainCoarse, (uint32_t)vbase >> 4);
+      float l[kSampleLaneElems];
+#pragma unroll
+      for (int k = 0; k < kVecs; ++k) {
+        float e[kPer];
+        DT::unpack(raw[k], e);
+#pragma unroll
+        for (int j = 0; j < kPer; ++j) l[k * kPer + j] = e[j];
+      }
+      if (!first) load_tile(raw, tile0 + kDepth * kTile);
+      if (kFast && tile0 > v_end - kTile) {  // uniform: the chunk's last, partial tile
+#pragma unroll
+        for (int j = 0; j < kSampleLaneElems; ++j) l[j] = vbase + j < v_end ? l[j] : -INFINITY;
+      }
+      // bit 7 of a byte of fl is set iff that byte of the noise word is 255
+      uint32_t pm = 0u;
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        const uint32_t w = coarse.word(k);
+        const uint32_t fl = ((w & 0x7F7F7F7Fu) + 0x01010101u) & w & 0x80808080u;
+        pm |= fl >> (7 - k);
+      }
+      pend_pm = pm;
+      pend_vb = vbase;
+      pend_w0 = coarse.w0; pend_w1 = coarse.w1; pend_w2 = coarse.w2; pend_w3 = coarse.w3;
+      float lmax = l[0];
+#pragma unroll
+      for (int j = 1; j < kSampleLaneElems; ++j) lmax = fmaxf(lmax, l[j]);
+      return lmax;
+    };
+
+    // First tile: a threshold before anything is tested against one.  The entries with coarse byte
+    // 255 of every wave's first tile go through level 2 together (about 64 of them for 16 waves: a
+    // threshold within a few units of the final one); the lanes' other entries are tested against
+    // the threshold that gives.
+    {
+      const float lmax = tile_noise(raw0, v_begin, true);
+      settle();
+      // Memory serves a compute unit's requests in order, so the later tiles are only requested
+      // now, when every wave's first tile has long been requested: they arrive while the first
+      // threshold is worked out.
+      __builtin_amdgcn_sched_barrier(0);
+      load_tile(raw1, v_begin + kTile);
+      if (kDepth == 4) {
+        load_tile(raw2, v_begin + 2 * kTile);
+        load_tile(raw3, v_begin + 3 * kTile);
+      }
+      load_tile(raw0, v_begin + kDepth * kTile);
+      __builtin_amdgcn_sched_barrier(0);
+      pool_evaluate(0);
+      tile_groups(lmax, v_begin);
+      settle();
+    }
+    // The other tiles, kDepth at a time, each from its own buffer.  Both queues hold at most 63
+    // entries when a step that appends (at most 64) starts.
+    for (int tile0 = v_begin + kTile; tile0 < v_end; tile0 += kDepth * kTile) {
+#pragma unroll
+      for (int u = 0; u < kDepth; ++u) {
+        const int t0 = tile0 + u * kTile;
+        if (t0 < v_end) {  // uniform
+          adopt_threshold();
+          const int turn = (u + 1) & (kDepth - 1);
+          const float lmax = tile_noise(turn == 0 ? raw0 : (turn == 1 ? raw1 : (turn == 2 ? raw2 : raw3)), t0, false);
+          tile_groups(lmax, t0);
+          settle();
         }
       }
     }
-  }
-  if (qcount > 0) evaluate_batch(qcount);
-  compact_survivors();
+  };
+  if (vector_ok && V % kPer == 0 && v_end - v_begin >= kPer) stream(std::true_type{});
+  else stream(std::false_type{});
 
-  // ---- merge the four waves into this chunk's record -------------------------------------------
-  if (lane == 0) sh_theta[wave] = theta;
+  // ---- no tiles left: this wave's queued groups, then the queued entries of all waves together -----
+  while (gcount > 0) {
+    adopt_threshold();
+    const int cnt = gcount < kWave ? gcount : kWave;
+    gcount -= cnt;
+    inspect_groups(q0 + gcount, cnt);
+    settle();
+  }
+  pool_evaluate(2);
+  compact_survivors();
+  publish_threshold();
+
+  // ---- merge the waves' survivors into this chunk's record ---------------------------------------
   __syncthreads();
-  float theta_wg = sh_theta[g * kWavesPerBlock];
-#pragma unroll
-  for (int w = 1; w < kWavesPerBlock; ++w) theta_wg = fmaxf(theta_wg, sh_theta[g * kWavesPerBlock + w]);
+  // every wave of the workgroup has published its last threshold: this is the workgroup's
+  const float theta_wg = ordered_float(sh_theta_row);
   uint32_t* rec = p.records + ((size_t)b * p.S + s) * kRecordWords;
   {
     const bool have = lane < scount;
@@ -437,6 +668,7 @@ __device__ __forceinline__ void sample_body(const Problem& p) {
         rec[2 + 2 * slot] = (uint32_t)v;
         rec[3 + 2 * slot] = __float_as_uint(su);
       }
+      if (kFused) sh_only = v;
     }
     if (overflow && lane == 0) sh_overflow_g[g] = 1;
   }
@@ -446,11 +678,23 @@ __device__ __forceinline__ void sample_body(const Problem& p) {
     rec[1] = (sh_overflow_g[g] || sh_count_g[g] > kRecordCap) ? (uint32_t)kRecordOverflow
                                                             : (uint32_t)sh_count_g[g];
   }
+  if (kFused) {
+    // exactly one entry of the whole row survived: it is the winner, nothing to compare it with
+    int total = 0, any_overflow = 0;
+#pragma unroll
+    for (int i = 0; i < G; ++i) { total += sh_count_g[i]; any_overflow |= sh_overflow_g[i]; }
+    const bool separable = theta_wg > (residual ? kDegenerate : kNoThreshold);
+    if (separable && !any_overflow && total == 1) {
+      if (threadIdx.x == 0) p.out_tokens[r0 + b + n] = sh_only;
+      return true;
+    }
+  }
+  return false;
 }
 
 template <typename DT, bool kLate>
 __global__ __launch_bounds__(kBlock) void sample_kernel(Problem p) {
-  sample_body<DT, 1, kLate>(p);
+  (void)sample_body<DT, 1, kLate, false>(p);
 }
 
 // Level 3.  One workgroup per sequence reads the chunk records of the filter kernel.  A single
@@ -639,9 +883,9 @@ __global__ __launch_bounds__(kBlock) void select_kernel(Problem p) {
 // 80 (three 512-thread groups per CU, as the filter alone); the others run one or two groups per
 // CU whatever they use.
 template <typename DT, int G, bool kLate>
-__global__ __launch_bounds__(kBlock* G, (G == 1 && !kLate && sizeof(typename DT::storage) == 2) ? 6 : 4)
+__global__ __launch_bounds__(kBlock* G, 4)
 void sample_select_kernel(Problem p) {
-  sample_body<DT, G, kLate>(p);
+  if (sample_body<DT, G, kLate, true>(p)) return;  // uniform over the workgroup
   __syncthreads();
   if ((int)threadIdx.x >= kBlock) return;  // whole waves
   select_body<DT>(p, (int)blockIdx.y);
