@@ -148,8 +148,9 @@ __device__ __forceinline__ Philox philox4x32_10(uint32_t c0, uint32_t c1, uint32
   for (int i = 0; i < 10; ++i) {
     const uint64_t a = (uint64_t)0xD2511F53u * c0;
     const uint64_t b = (uint64_t)0xCD9E8D57u * c2;
-    const uint32_t n0 = (uint32_t)(b >> 32) ^ c1 ^ k0;
-    const uint32_t n2 = (uint32_t)(a >> 32) ^ c3 ^ k1;
+    // three-way exclusive or in one instruction (truth table 0x96)
+    const uint32_t n0 = __builtin_amdgcn_bitop3_b32((uint32_t)(b >> 32), c1, k0, 0x96);
+    const uint32_t n2 = __builtin_amdgcn_bitop3_b32((uint32_t)(a >> 32), c3, k1, 0x96);
     c1 = (uint32_t)b;
     c3 = (uint32_t)a;
     c0 = n0;
@@ -179,6 +180,14 @@ __device__ __forceinline__ double accept_uniform(uint64_t seed, uint64_t seq, ui
   return (double)(noise_block(seed, seq, pos, 0u, 0u).w0 >> 8) * 0x1p-24;
 }
 constexpr uint32_t kDomainAccept = 0u, kDomainCoarse = 1u, kDomainFine = 2u;
+
+// Workgroup barrier that orders LDS accesses only.  __syncthreads() also waits for every global
+// load the wave has in flight, which stalls a wave that keeps loads of later data outstanding.
+__device__ __forceinline__ void lds_barrier() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+  __builtin_amdgcn_s_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
 
 // ---- wave64 all-reduce through DPP / swizzle / permlane ---------------------------------------
 // After the call every lane of the wave holds the reduction.  Steps: xor 1 and xor 2 inside a

@@ -243,7 +243,7 @@ __device__ __forceinline__ bool sample_body(const Problem& p) {
     // (the same few words for all of them), the first wave of the row's first chunk stores the
     // accept length and the accepted prefix
     n = first_reject_scan(p, b, lane, true, s == 0 && wave_g == 0);
-    __syncthreads();  // thresholds initialised before any wave reads another's
+    lds_barrier();  // thresholds initialised before any wave reads another's
   } else {
     if (kLate) {
       // the decisions are taken here from the cached statistics, by one wave
@@ -255,7 +255,7 @@ __device__ __forceinline__ bool sample_body(const Problem& p) {
       const int nn = p.accept_len[b];
       sh_n = nn < 0 ? 0 : (nn > Kb ? Kb : nn);
     }
-    __syncthreads();
+    lds_barrier();
     n = sh_n;
   }
   n = __builtin_amdgcn_readfirstlane(n);
@@ -525,12 +525,12 @@ __device__ __forceinline__ bool sample_body(const Problem& p) {
       sh_ent_h[kPool + base + lane] = sh_ent_h[q0 + lane];
     }
     qcount = 0;
-    __syncthreads();
+    lds_barrier();
     const int total = sh_pool_n[which];
     adopt_threshold();
     for (int b0 = wave * kWave; b0 < total; b0 += kWaves * kWave)
       evaluate_batch(kPool + b0, total - b0 < kWave ? total - b0 : kWave);
-    __syncthreads();
+    lds_barrier();
     adopt_threshold();
   };
 
@@ -595,16 +595,17 @@ __device__ __forceinline__ bool sample_body(const Problem& p) {
       return lmax;
     };
 
-    // First tile: a threshold before anything is tested against one.  The entries with coarse byte
-    // 255 of every wave's first tile go through level 2 together (about 64 of them for 16 waves: a
-    // threshold within a few units of the final one); the lanes' other entries are tested against
-    // the threshold that gives.
+    // First tiles: a threshold before anything is tested against one.  Every wave draws the noise
+    // of its first kDepth tiles as their data arrive and queues their entries with coarse byte 255;
+    // those of all waves then go through level 2 together (a few hundred entries: a threshold
+    // within a few units of the final one), and only then are the lanes' other entries of these
+    // tiles tested.  That keeps the vector units busy while the first half of the row is on its way.
+    // Memory serves a compute unit's requests in order, so the later tiles are only requested when
+    // every wave's first tile has long been requested.
     {
-      const float lmax = tile_noise(raw0, v_begin, true);
+      float lmax0, lmax1 = -INFINITY, lmax2 = -INFINITY, lmax3 = -INFINITY;
+      lmax0 = tile_noise(raw0, v_begin, true);
       settle();
-      // Memory serves a compute unit's requests in order, so the later tiles are only requested
-      // now, when every wave's first tile has long been requested: they arrive while the first
-      // threshold is worked out.
       __builtin_amdgcn_sched_barrier(0);
       load_tile(raw1, v_begin + kTile);
       if (kDepth == 4) {
@@ -613,20 +614,39 @@ __device__ __forceinline__ bool sample_body(const Problem& p) {
       }
       load_tile(raw0, v_begin + kDepth * kTile);
       __builtin_amdgcn_sched_barrier(0);
+      if (v_begin + kTile < v_end) {
+        lmax1 = tile_noise(raw1, v_begin + kTile, false);
+        settle();
+      }
+      if (kDepth == 4 && v_begin + 2 * kTile < v_end) {
+        lmax2 = tile_noise(raw2, v_begin + 2 * kTile, false);
+        settle();
+      }
+      if (kDepth == 4 && v_begin + 3 * kTile < v_end) {
+        lmax3 = tile_noise(raw3, v_begin + 3 * kTile, false);
+        settle();
+      }
       pool_evaluate(0);
-      tile_groups(lmax, v_begin);
+      tile_groups(lmax0, v_begin);
       settle();
+      tile_groups(lmax1, v_begin + kTile);
+      settle();
+      if (kDepth == 4) {
+        tile_groups(lmax2, v_begin + 2 * kTile);
+        settle();
+        tile_groups(lmax3, v_begin + 3 * kTile);
+        settle();
+      }
     }
-    // The other tiles, kDepth at a time, each from its own buffer.  Both queues hold at most 63
+    // The other tiles, kDepth at a time, each from its own buffer.  Both queues hold at most 63 / 64
     // entries when a step that appends (at most 64) starts.
-    for (int tile0 = v_begin + kTile; tile0 < v_end; tile0 += kDepth * kTile) {
+    for (int tile0 = v_begin + kDepth * kTile; tile0 < v_end; tile0 += kDepth * kTile) {
 #pragma unroll
       for (int u = 0; u < kDepth; ++u) {
         const int t0 = tile0 + u * kTile;
         if (t0 < v_end) {  // uniform
           adopt_threshold();
-          const int turn = (u + 1) & (kDepth - 1);
-          const float lmax = tile_noise(turn == 0 ? raw0 : (turn == 1 ? raw1 : (turn == 2 ? raw2 : raw3)), t0, false);
+          const float lmax = tile_noise(u == 0 ? raw0 : (u == 1 ? raw1 : (u == 2 ? raw2 : raw3)), t0, false);
           tile_groups(lmax, t0);
           settle();
         }
@@ -649,7 +669,7 @@ __device__ __forceinline__ bool sample_body(const Problem& p) {
   publish_threshold();
 
   // ---- merge the waves' survivors into this chunk's record ---------------------------------------
-  __syncthreads();
+  lds_barrier();
   // every wave of the workgroup has published its last threshold: this is the workgroup's
   const float theta_wg = ordered_float(sh_theta_row);
   uint32_t* rec = p.records + ((size_t)b * p.S + s) * kRecordWords;
@@ -672,7 +692,7 @@ __device__ __forceinline__ bool sample_body(const Problem& p) {
     }
     if (overflow && lane == 0) sh_overflow_g[g] = 1;
   }
-  __syncthreads();
+  lds_barrier();
   if (tid == 0) {
     rec[0] = __float_as_uint(theta_wg);
     rec[1] = (sh_overflow_g[g] || sh_count_g[g] > kRecordCap) ? (uint32_t)kRecordOverflow
