@@ -37,6 +37,12 @@
  *    device status word.
  *  - Two calls that share a workspace (or the library-owned scratch of the simple entry points)
  *    must not overlap in time.
+ *  - EARS_ERR_HIP reports a failure of this call's own launches.  HIP keeps one "last error" per
+ *    host thread: every call that launches work clears it first, so an error left pending by the
+ *    caller's earlier HIP calls is neither reported here nor left for the caller to read.
+ *  - Range of the arithmetic: the sampling stage bounds scores in fp32 with fixed margins that
+ *    cover |logit| / T up to about 1e3 (e.g. |logit| <= 20 at T >= 0.02); beyond that a replacement
+ *    or bonus token may differ from the fp64 definition's.  Accept lengths are not affected.
  */
 #ifndef EARS_H
 #define EARS_H
@@ -51,7 +57,8 @@ extern "C" {
 typedef enum ears_status {
   EARS_OK = 0,
   EARS_ERR_NULL = 1,      /* a required pointer is NULL */
-  EARS_ERR_SHAPE = 2,     /* B, K, V or total_draft_rows out of range */
+  EARS_ERR_SHAPE = 2,     /* B, K, V or total_draft_rows out of range (also: more than 2^30 draft
+                             rows, or more sampling workgroups than a launch can hold) */
   EARS_ERR_PARAM = 3,     /* temperature not finite or <= 0; beta not finite or < 0; bad stages
                              or uncertainty measure */
   EARS_ERR_ALIGN = 4,     /* a pointer is not aligned as documented */
@@ -131,7 +138,10 @@ int ears_verify_bf16(const void* target_logits, const void* draft_logits,
  *   target_logits    [total_draft_rows + B, V]: the K_b + 1 target rows of sequence b start at
  *                    packed row row_offsets[b] + b
  *   draft_logits     [total_draft_rows, V]; draft_tokens [total_draft_rows]
- *   temperature,beta [B] float32, device, per sequence (each T > 0, beta >= 0; not checked)
+ *   temperature,beta [B] float32, device, per sequence (each T > 0, beta >= 0, finite).  They
+ *                    cannot be checked on the host: a sequence whose T is not a positive finite
+ *                    number is verified with T = 1, one whose beta is negative or not finite with
+ *                    beta = 0, and bit 3 of the status word is raised
  *   out_accept_len   [B]; out_tokens [total_draft_rows + B], packed like the target rows
  * ------------------------------------------------------------------------------------------- */
 int ears_verify_ragged_f32(const float* target_logits, const float* draft_logits,
@@ -181,6 +191,8 @@ size_t ears_workspace_bytes(int64_t total_draft_rows, int B, int V);
  *                            positive finite number (a NaN or +inf logit, or no finite entry at
  *                            all): the results of that sequence are undefined, the others' are
  *                            not affected
+ *                    bit 3 = a per-sequence temperature was not a positive finite number (1 was
+ *                            used) or a per-sequence beta was negative or not finite (0 was used)
  * ------------------------------------------------------------------------------------------- */
 int ears_verify_ex(int dtype, const void* target_logits, const void* draft_logits,
                    const int32_t* draft_tokens, const int64_t* row_offsets,

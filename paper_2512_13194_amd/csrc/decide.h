@@ -84,6 +84,7 @@ __device__ __forceinline__ int first_reject_scan(const Problem& p, int b, int la
         // decision falls back to 1 - max P_t = 1 - 1/Z_t and says so in the status word.
         const bool cached = p.unc_mode != 0 && *p.unc_tag == (uint32_t)p.unc_mode;
         if (p.unc_mode != 0 && !cached && i == 0 && p.status_word) atomicOr(p.status_word, 2u);
+        if (i == 0 && p.status_word && seq_params_invalid(p, b)) atomicOr(p.status_word, 8u);
         const double unc = cached ? p.unc[r] : 1.0 - 1.0 / Zt;
         const double U = accept_uniform(p.seed, seq_rng_id(p, b), (uint32_t)i);
         decision = decide_position(p, b, r, p.tokens[r], U, (double)p.m[2 * r], Zt,
@@ -104,7 +105,7 @@ __device__ __forceinline__ int first_reject_scan(const Problem& p, int b, int la
   return n;
 }
 
-// Stand-alone decision stage: four sequences per workgroup, one per wave.  Slot n of out_tokens
+// Stand-alone decision stage: kWavesPerBlock sequences per workgroup, one per wave.  Slot n of out_tokens
 // is set to -1 here; the sampling stage overwrites it.
 __global__ __launch_bounds__(kBlock) void decide_kernel(Problem p) {
   const int lane = (int)threadIdx.x & (kWave - 1);

@@ -80,11 +80,22 @@ __device__ __forceinline__ int64_t seq_row_begin(const Problem& p, int b) {
 __device__ __forceinline__ int seq_len(const Problem& p, int b) {
   return p.row_offsets ? (int)(p.row_offsets[b + 1] - p.row_offsets[b]) : p.K;
 }
+// Per-sequence parameters come from device memory and cannot be checked on the host: a
+// temperature that is not a positive finite number is replaced by 1, a beta that is negative or
+// not finite by 0 (so that the sequence's arithmetic stays finite), and the statistics / decision
+// stage raises status bit 3.
 __device__ __forceinline__ float seq_temperature(const Problem& p, int b) {
-  return p.T_seq ? p.T_seq[b] : p.T;
+  const float T = p.T_seq ? p.T_seq[b] : p.T;
+  return (T > 0.0f && T < INFINITY) ? T : 1.0f;
 }
 __device__ __forceinline__ float seq_beta(const Problem& p, int b) {
-  return p.beta_seq ? p.beta_seq[b] : p.beta;
+  const float beta = p.beta_seq ? p.beta_seq[b] : p.beta;
+  return (beta >= 0.0f && beta < INFINITY) ? beta : 0.0f;
+}
+__device__ __forceinline__ bool seq_params_invalid(const Problem& p, int b) {
+  const float T = p.T_seq ? p.T_seq[b] : p.T;
+  const float beta = p.beta_seq ? p.beta_seq[b] : p.beta;
+  return !(T > 0.0f && T < INFINITY) || !(beta >= 0.0f && beta < INFINITY);
 }
 __device__ __forceinline__ uint64_t seq_rng_id(const Problem& p, int b) {
   return p.seq_ids ? (uint64_t)p.seq_ids[b] : (uint64_t)b;
@@ -175,7 +186,7 @@ __device__ __forceinline__ Philox noise_block(uint64_t seed, uint64_t seq, uint3
                        (uint32_t)seed, (uint32_t)(seed >> 32));
 }
 
-// U in [0,1) on a 2^-24 grid; u in (0,1) on a 2^-23 grid offset by 2^-24.  Both exact in fp32.
+// Acceptance uniform U in [0,1) on a 2^-24 grid (exact in fp32).
 __device__ __forceinline__ double accept_uniform(uint64_t seed, uint64_t seq, uint32_t pos) {
   return (double)(noise_block(seed, seq, pos, 0u, 0u).w0 >> 8) * 0x1p-24;
 }
@@ -193,7 +204,7 @@ __device__ __forceinline__ void lds_barrier() {
 // After the call every lane of the wave holds the reduction.  Steps: xor 1 and xor 2 inside a
 // quad (quad_perm), then mirror inside 8 and 16 lanes (row_half_mirror, row_mirror; valid because
 // the earlier steps made each quad / half-row uniform), then swap 16-lane rows inside each half
-// (ds_swizzle) and finally the two halves (v_permlane32_swap via readlane-free builtin).
+// (ds_swizzle) and finally the two halves (a cross-lane shuffle).
 template <int kCtrl>
 __device__ __forceinline__ float dpp_f32(float v) {
   return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), kCtrl, 0xF, 0xF, false));

@@ -78,6 +78,8 @@ static bool workspace_layout(int64_t R, int B, int V, WorkspaceLayout* w) {
   w->off_decisions = o; o = align_up(o + (size_t)R * sizeof(int32_t), 256);
   w->off_records = o;  o = align_up(o + (size_t)B * S4 * kRecordWords * sizeof(uint32_t), 256);
   w->total = o;
+  w->S = S4;
+  w->chunk = chunk;
   return true;
 }
 
@@ -97,6 +99,9 @@ static int validate(int dtype, const void* target, const void* draft, const int3
     if (K < 1 || (int64_t)B * (int64_t)K != R) return EARS_ERR_SHAPE;
   }
   if (!workspace_layout(R, B, V, lay)) return EARS_ERR_SHAPE;
+  // every launch is one-dimensional; the largest is rows (bounded above) or workgroups of the
+  // sampling stage, B times the chunks of a row
+  if ((int64_t)B * (int64_t)lay->S > (int64_t)0x7FFFFFFF) return EARS_ERR_SHAPE;
   if (stages < 1 || stages > EARS_STAGE_ALL) return EARS_ERR_PARAM;
   if (!T_seq && !(std::isfinite(T) && T > 0.0f)) return EARS_ERR_PARAM;
   if (!beta_seq && !(std::isfinite(beta) && beta >= 0.0f)) return EARS_ERR_PARAM;
@@ -115,13 +120,14 @@ static int validate(int dtype, const void* target, const void* draft, const int3
 template <typename DT, bool kLate>
 static void launch_sample(const Problem& p, hipStream_t stream) {
   if (p.S == 1) {
-    hipLaunchKernelGGL((sample_select_kernel<DT, 1, kLate>), dim3(1u, (unsigned)p.B), dim3(kBlock), 0,
+    hipLaunchKernelGGL((sample_select_kernel<DT, 1, kLate>), dim3((unsigned)p.B), dim3(kBlock), 0,
                        stream, p);
   } else if (p.S == 2) {
-    hipLaunchKernelGGL((sample_select_kernel<DT, 2, kLate>), dim3(1u, (unsigned)p.B), dim3(2 * kBlock),
+    hipLaunchKernelGGL((sample_select_kernel<DT, 2, kLate>), dim3((unsigned)p.B), dim3(2 * kBlock),
                        0, stream, p);
   } else {
-    hipLaunchKernelGGL((sample_kernel<DT, kLate>), dim3((unsigned)p.S, (unsigned)p.B), dim3(kBlock), 0,
+    // (S * B fits a grid: checked with the other shapes)
+    hipLaunchKernelGGL((sample_kernel<DT, kLate>), dim3((unsigned)p.S * (unsigned)p.B), dim3(kBlock), 0,
                        stream, p);
     hipLaunchKernelGGL((select_kernel<DT>), dim3((unsigned)p.B), dim3(kBlock), 0, stream, p);
   }
@@ -129,6 +135,7 @@ static void launch_sample(const Problem& p, hipStream_t stream) {
 
 template <typename DT>
 static int launch(Problem p, int stages, hipStream_t stream) {
+  (void)hipGetLastError();  // a stale error of the caller's own HIP calls is not this call's
   sample_split(p.B, p.V, kSampleTileElems, &p.S, &p.chunk);
   const bool stats = (stages & EARS_STAGE_STATS) != 0;
   const bool decide = (stages & EARS_STAGE_DECIDE) != 0;
@@ -428,6 +435,7 @@ int ears_verify_greedy(int dtype, const void* target_logits, const int32_t* draf
     const int rc = scratch_get(need, &workspace);
     if (rc != EARS_OK) return rc;
   }
+  (void)hipGetLastError();  // a stale error of the caller's own HIP calls is not this call's
   GreedyProblem p;
   p.target = target_logits;
   p.tokens = draft_tokens;
@@ -473,6 +481,7 @@ int ears_lm_head_bf16(const void* hidden, const void* weight, int N, int D, int 
   const size_t need = ears_lm_head_workspace_bytes(N, V);
   if (!workspace || workspace_bytes < need) return EARS_ERR_WORKSPACE;
   if (!aligned(workspace, 256)) return EARS_ERR_ALIGN;
+  (void)hipGetLastError();  // a stale error of the caller's own HIP calls is not this call's
   LmHeadProblem p;
   p.hidden = static_cast<const uint16_t*>(hidden);
   p.weight = static_cast<const uint16_t*>(weight);
@@ -510,6 +519,7 @@ int ears_row_stats(int dtype, const void* logits, int64_t rows, int V, float tem
   if (!aligned(logits, 16) || !aligned(out_row_max, 4) || !aligned(out_row_sumexp, 8) ||
       !aligned(out_row_entropy, 8) || !aligned(row_temperature, 4))
     return EARS_ERR_ALIGN;
+  (void)hipGetLastError();  // a stale error of the caller's own HIP calls is not this call's
   RowStatsProblem p;
   p.logits = logits;
   p.rows = rows;
@@ -551,6 +561,7 @@ int ears_import_stats(int dtype, const void* target_logits, const void* draft_lo
   if (!aligned(target_row_max, 4) || !aligned(draft_row_max, 4) || !aligned(target_row_sumexp, 8) ||
       !aligned(draft_row_sumexp, 8) || !aligned(target_row_entropy, 8))
     return EARS_ERR_ALIGN;
+  (void)hipGetLastError();  // a stale error of the caller's own HIP calls is not this call's
   Problem p = {};
   p.target = target_logits;
   p.draft = draft_logits;
@@ -583,7 +594,8 @@ int ears_bench_read(const void* src, size_t bytes, uint32_t* sink, void* stream)
   if (!src || !sink) return EARS_ERR_NULL;
   if (bytes == 0 || bytes % 16 != 0) return EARS_ERR_SHAPE;
   if (!aligned(src, 16) || !aligned(sink, 4)) return EARS_ERR_ALIGN;
-  // slabs of about 256 KiB, their number a multiple of 1024 (four 512-thread workgroups on each
+  (void)hipGetLastError();
+  // slabs of about 256 KiB, their number a multiple of 1024 (four workgroups of kBlock threads on each
   // of 256 CUs) so that the last round of workgroups is a full one
   const size_t nvec = bytes / 16;
   size_t rounds = (nvec + 1024 * kBenchSlabVecs / 2) / (1024 * kBenchSlabVecs);
@@ -602,6 +614,7 @@ int ears_bench_copy(void* dst, const void* src, size_t bytes, void* stream) {
   if (!src || !dst) return EARS_ERR_NULL;
   if (bytes == 0 || bytes % 16 != 0) return EARS_ERR_SHAPE;
   if (!aligned(src, 16) || !aligned(dst, 16)) return EARS_ERR_ALIGN;
+  (void)hipGetLastError();
   hipLaunchKernelGGL(bench_copy_kernel, dim3(kBenchBlocks), dim3(kBlock), 0,
                      static_cast<hipStream_t>(stream), static_cast<uint4*>(dst),
                      static_cast<const uint4*>(src), bytes / 16);

@@ -17,7 +17,7 @@ namespace ears {
 // so the running maximum changes (and S is rescaled) at most once per chunk and the inner loop
 // is one FMA, one v_exp_f32 and one add per element.  The lanes are merged with the associative
 // rule (m,S) + (m',S') = (M, S*2^(mc-Mc) + S'*2^(m'c-Mc)), M = max(m,m'): a DPP wave reduction of
-// the maxima, a per-lane rescale, an fp64 DPP wave sum, and an LDS combine of the four waves.
+// the maxima, a per-lane rescale, an fp64 DPP wave sum, and an LDS combine of the workgroup's waves.
 // The rounding of fl(M*c) is removed exactly at the end in fp64, so Z = sum exp((l - M)/T) carries
 // only the fp32 rounding of the individual terms.  max P = 1/Z needs no second pass
 // (Section 3.3 item 1: the maximum is cached, the row is never re-scanned for it).
@@ -205,6 +205,7 @@ __global__ __launch_bounds__(kBlock) void row_stats_kernel(Problem p) {
     // a NaN or +inf logit, or a row without any finite entry, leaves Z outside (0, inf)
     if (p.status_word && !(Zt > 0.0 && Zt < INFINITY && Zd > 0.0 && Zd < INFINITY))
       atomicOr(p.status_word, 4u);
+    if (p.status_word && seq_params_invalid(p, b)) atomicOr(p.status_word, 8u);
     if (kDecide)
       p.decisions[r] = decide_position(p, b, r, x, U, (double)Mt, Zt, (double)lxt, (double)Md, Zd,
                                        (double)lxd, unc);

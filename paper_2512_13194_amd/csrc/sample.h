@@ -228,7 +228,10 @@ __device__ __forceinline__ bool sample_body(const Problem& p) {
   const int g = wave / kWavesPerBlock;                     // sub-block
   const int wave_g = wave - g * kWavesPerBlock;            // wave within the sub-block
   const int tid = (int)threadIdx.x - g * kBlock, lane = (int)threadIdx.x & (kWave - 1);
-  const int s = (int)blockIdx.x * G + g, b = (int)blockIdx.y;
+  // workgroups are numbered along x: all those of a row one after the other
+  const int groups_per_row = kFused ? 1 : p.S;
+  const int b = (int)(blockIdx.x / (unsigned)groups_per_row);
+  const int s = ((int)blockIdx.x - b * groups_per_row) * G + g;
   const int V = p.V;
 
   // ---- accept length of this sequence ---------------------------------------------------------
@@ -668,11 +671,15 @@ __device__ __forceinline__ bool sample_body(const Problem& p) {
   compact_survivors();
   publish_threshold();
 
-  // ---- merge the waves' survivors into this chunk's record ---------------------------------------
+  // ---- merge the waves' survivors into the workgroup's records -------------------------------------
+  // The waves share their level-2 work, so a wave's survivors come from anywhere in the
+  // workgroup's range: they fill the workgroup's G records one after the other, and what neither a
+  // wave nor the records could hold makes every one of them say "overflow" (the exact choice then
+  // scans the whole range).
   lds_barrier();
   // every wave of the workgroup has published its last threshold: this is the workgroup's
   const float theta_wg = ordered_float(sh_theta_row);
-  uint32_t* rec = p.records + ((size_t)b * p.S + s) * kRecordWords;
+  uint32_t* rec0 = p.records + ((size_t)b * p.S + (s - g)) * kRecordWords;  // the first of the G records
   {
     const bool have = lane < scount;
     const int v = have ? sh_surv_v[wave][lane] : 0;
@@ -680,29 +687,31 @@ __device__ __forceinline__ bool sample_body(const Problem& p) {
     const bool keep = have && su >= theta_wg;
     const unsigned long long km = __ballot(keep);
     int base = 0;
-    if (lane == 0 && km != 0ull) base = atomicAdd(&sh_count_g[g], __popcll(km));
+    if (lane == 0 && km != 0ull) base = atomicAdd(&sh_count_g[0], __popcll(km));
     base = __shfl(base, 0, 64);
     if (keep) {
       const int slot = base + lanes_below(km);
-      if (slot < kRecordCap) {
-        rec[2 + 2 * slot] = (uint32_t)v;
-        rec[3 + 2 * slot] = __float_as_uint(su);
+      if (slot < G * kRecordCap) {
+        uint32_t* rec = rec0 + (slot / kRecordCap) * kRecordWords;
+        rec[2 + 2 * (slot % kRecordCap)] = (uint32_t)v;
+        rec[3 + 2 * (slot % kRecordCap)] = __float_as_uint(su);
       }
       if (kFused) sh_only = v;
     }
-    if (overflow && lane == 0) sh_overflow_g[g] = 1;
+    if (overflow && lane == 0) sh_overflow_g[0] = 1;
   }
   lds_barrier();
+  const int total = sh_count_g[0];
+  const bool any_overflow = sh_overflow_g[0] != 0 || total > G * kRecordCap;
   if (tid == 0) {
+    uint32_t* rec = rec0 + g * kRecordWords;
+    const int mine = total - g * kRecordCap;
     rec[0] = __float_as_uint(theta_wg);
-    rec[1] = (sh_overflow_g[g] || sh_count_g[g] > kRecordCap) ? (uint32_t)kRecordOverflow
-                                                            : (uint32_t)sh_count_g[g];
+    rec[1] = any_overflow ? (uint32_t)kRecordOverflow
+                          : (uint32_t)(mine < 0 ? 0 : (mine > kRecordCap ? kRecordCap : mine));
   }
   if (kFused) {
     // exactly one entry of the whole row survived: it is the winner, nothing to compare it with
-    int total = 0, any_overflow = 0;
-#pragma unroll
-    for (int i = 0; i < G; ++i) { total += sh_count_g[i]; any_overflow |= sh_overflow_g[i]; }
     const bool separable = theta_wg > (residual ? kDegenerate : kNoThreshold);
     if (separable && !any_overflow && total == 1) {
       if (threadIdx.x == 0) p.out_tokens[r0 + b + n] = sh_only;
@@ -908,7 +917,7 @@ void sample_select_kernel(Problem p) {
   if (sample_body<DT, G, kLate, true>(p)) return;  // uniform over the workgroup
   __syncthreads();
   if ((int)threadIdx.x >= kBlock) return;  // whole waves
-  select_body<DT>(p, (int)blockIdx.y);
+  select_body<DT>(p, (int)blockIdx.x);
 }
 
 }  // namespace ears

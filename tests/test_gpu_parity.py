@@ -236,6 +236,34 @@ def test_residual_support_floor_on_nearly_identical_peaked_rows(ears, oracle):
         assert (ora.accept_len == 0).sum() > B // 2
 
 
+def test_survivors_beyond_one_record_are_not_lost(ears, oracle):
+    """Sharply peaked, nearly identical rows at a low temperature: in some sequences the residual
+    lives only in the difference of the two normalisers, the fp32 bounds cannot rank its entries,
+    and a row ends with more surviving entries than one record holds.  (Found by a randomised sweep:
+    the entries that did not fit had been counted against one half of the row only.)"""
+    from paper_2512_13194_amd import inputs
+    _log("survivors beyond one record")
+    B, K, V, T, beta, seed = 300, 1, 16384, 0.3, 0.1, 7582074434628525484
+    batch = inputs.make_rect(B, K, V, torch.bfloat16, T=T, data_seed=999050555, sigma_lo=0.2, sigma_hi=12.0,
+                             draft_noise=0.01, peaked_frac=0.2, device="cuda")
+    g = torch.Generator(device="cuda").manual_seed(1)
+    batch.tokens = torch.randint(0, V, (B, K), device="cuda", dtype=torch.int32, generator=g)
+    for unc in (0, 1):
+        rep, ora, _ = run_rect(ears, oracle, batch, T, beta, seed, uncertainty=unc)
+        assert rep.exempt_decisions == 0 and rep.exempt_tokens == 0
+    # the same with part of the vocabulary masked
+    batch.target[:, :, V - V // 7:] = float("-inf")
+    batch.draft[:, :, V - V // 7:] = float("-inf")
+    batch.tokens = batch.tokens.clamp(max=V - V // 7 - 1)
+    rep, ora, _ = run_rect(ears, oracle, batch, T, beta, seed, uncertainty=1)
+    assert rep.exempt_decisions == 0 and rep.exempt_tokens == 0
+    # one of those sequences on its own (the row split differently), under its own RNG id
+    one = inputs.Batch(target=batch.target[278:279].contiguous(), draft=batch.draft[278:279].contiguous(),
+                       tokens=batch.tokens[278:279].contiguous(), B=1, V=V, K=K)
+    rep, ora, _ = run_rect(ears, oracle, one, T, beta, seed, seq_ids=np.array([278]), uncertainty=1)
+    assert rep.exempt_decisions == 0 and rep.exempt_tokens == 0
+
+
 def test_small_terms_beside_a_dominant_one_are_kept(ears, oracle):
     """A wide row with one entry far above the rest: Z = 1 + 3e-4, made of one term of 1 and 128255
     terms of ~2e-9.  A lane that adds those to a running sum near 1 in plain fp32 rounds every chunk
