@@ -150,21 +150,21 @@ static int launch(Problem p, int stages, hipStream_t stream) {
   p.decide_fused = fused ? 1 : (late ? 2 : 0);
   if (stats) {
     const dim3 grid((unsigned)p.R), block(kBlock);
-    if (fused) {
-      if (p.unc_mode == EARS_UNCERTAINTY_ENTROPY)
-        hipLaunchKernelGGL((row_stats_kernel<DT, 4, true, kMeasureEntropy>), grid, block, 0, stream, p);
-      else if (p.unc_mode == EARS_UNCERTAINTY_VARIANCE)
-        hipLaunchKernelGGL((row_stats_kernel<DT, 4, true, kMeasureVariance>), grid, block, 0, stream, p);
-      else
-        hipLaunchKernelGGL((row_stats_kernel<DT, 4, true, kMeasureNone>), grid, block, 0, stream, p);
-    } else {
-      if (p.unc_mode == EARS_UNCERTAINTY_ENTROPY)
-        hipLaunchKernelGGL((row_stats_kernel<DT, 4, false, kMeasureEntropy>), grid, block, 0, stream, p);
-      else if (p.unc_mode == EARS_UNCERTAINTY_VARIANCE)
-        hipLaunchKernelGGL((row_stats_kernel<DT, 4, false, kMeasureVariance>), grid, block, 0, stream, p);
-      else
-        hipLaunchKernelGGL((row_stats_kernel<DT, 4, false, kMeasureNone>), grid, block, 0, stream, p);
+    // The kernel always takes each position's decision as it finishes it.  Only a call that runs
+    // all three stages uses it (the sampling stage scans the decisions); otherwise it is left in
+    // the workspace unused and reports nothing: the decision stage takes its own from the
+    // statistics, with the parameters of its own call.
+    Problem ps = p;
+    if (!fused) {
+      ps.out_stats = nullptr;
+      ps.out_path = nullptr;
     }
+    if (p.unc_mode == EARS_UNCERTAINTY_ENTROPY)
+      hipLaunchKernelGGL((row_stats_kernel<DT, 4, kMeasureEntropy>), grid, block, 0, stream, ps);
+    else if (p.unc_mode == EARS_UNCERTAINTY_VARIANCE)
+      hipLaunchKernelGGL((row_stats_kernel<DT, 4, kMeasureVariance>), grid, block, 0, stream, ps);
+    else
+      hipLaunchKernelGGL((row_stats_kernel<DT, 4, kMeasureNone>), grid, block, 0, stream, ps);
   }
   if (decide && !fused && !late) {
     hipLaunchKernelGGL(decide_kernel, dim3((unsigned)((p.B + kWavesPerBlock - 1) / kWavesPerBlock)),

@@ -8,9 +8,10 @@ namespace ears {
 
 // =================================================================================================
 // One workgroup per draft position r: it streams the target row paired with r, then the draft
-// row r, and so holds both rows' statistics when it is done.  With kDecide its first thread
-// evaluates the acceptance decision for the position on the spot (paper Section 3.2 steps 2-5),
-// so that the sampling stage only has to scan K flags per sequence.
+// row r, and so holds both rows' statistics when it is done.  Its first thread then evaluates the
+// acceptance decision for the position on the spot (paper Section 3.2 steps 2-5), so that the
+// sampling stage only has to scan K flags per sequence.  (A call that runs the statistics stage
+// on its own takes the decision too and leaves it unused: one kernel serves every call.)
 //
 // Each lane keeps a running maximum m and S = sum exp2(l*c - fl(m*c)), c = log2(e)/T, over the
 // elements it has seen.  A chunk of register-resident elements is first reduced to its maximum,
@@ -156,7 +157,7 @@ __device__ __forceinline__ void row_pass(const typename DT::storage* base, int V
   }
 }
 
-template <typename DT, int kUnroll, bool kDecide, int kMeasure>
+template <typename DT, int kUnroll, int kMeasure>
 __global__ __launch_bounds__(kBlock) void row_stats_kernel(Problem p) {
   using storage = typename DT::storage;
   __shared__ float sh_m[kWavesPerBlock];
@@ -179,8 +180,7 @@ __global__ __launch_bounds__(kBlock) void row_stats_kernel(Problem p) {
       lxt = DT::load(trow, x);
       lxd = DT::load(drow, x);
     }
-    if (kDecide)
-      U = accept_uniform(p.seed, seq_rng_id(p, b), (uint32_t)(r - seq_row_begin(p, b)));
+    U = accept_uniform(p.seed, seq_rng_id(p, b), (uint32_t)(r - seq_row_begin(p, b)));
   }
 
   float Mt = 0.0f, Md = 0.0f;
@@ -206,8 +206,7 @@ __global__ __launch_bounds__(kBlock) void row_stats_kernel(Problem p) {
     if (p.status_word && !(Zt > 0.0 && Zt < INFINITY && Zd > 0.0 && Zd < INFINITY))
       atomicOr(p.status_word, 4u);
     if (p.status_word && seq_params_invalid(p, b)) atomicOr(p.status_word, 8u);
-    if (kDecide)
-      p.decisions[r] = decide_position(p, b, r, x, U, (double)Mt, Zt, (double)lxt, (double)Md, Zd,
+    p.decisions[r] = decide_position(p, b, r, x, U, (double)Mt, Zt, (double)lxt, (double)Md, Zd,
                                        (double)lxd, unc);
   }
 }

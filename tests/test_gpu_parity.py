@@ -476,6 +476,68 @@ def test_non_finite_logits_are_flagged_and_stay_contained(ears, oracle):
     assert int(status.item()) == 0
 
 
+def test_bad_per_sequence_parameters_are_flagged_and_replaced(ears, oracle):
+    """Per-sequence temperatures and betas live in device memory and cannot be checked on the host:
+    a temperature that is not a positive finite number is replaced by 1, a beta that is negative or
+    not finite by 0, status bit 3 is raised, and every sequence (those included) matches the oracle
+    run with the replaced values."""
+    from paper_2512_13194_amd import inputs
+    _log("bad per-sequence parameters")
+    batch = inputs.make_ragged(24, 3001, torch.bfloat16, data_seed=95, device="cuda")
+    T = batch.temperature.clone()
+    beta = batch.beta.clone()
+    T[3], T[7], T[11] = 0.0, float("nan"), float("inf")
+    beta[5], beta[7], beta[13] = -0.5, float("nan"), float("inf")
+    status = torch.zeros(1, dtype=torch.int32, device="cuda")
+    out = ears.ears_verify_ex(batch.target, batch.draft, batch.tokens, row_offsets=batch.row_offsets,
+                              temperature_per_seq=T, beta_per_seq=beta, seed=21, want_stats=True,
+                              want_path=True, status_word=status)
+    torch.cuda.synchronize()
+    assert int(status.item()) & 8 == 8
+    T_used, beta_used = T.cpu().numpy().copy(), beta.cpu().numpy().copy()
+    T_used[[3, 7, 11]] = 1.0
+    beta_used[[5, 7, 13]] = 0.0
+    off = batch.row_offsets.cpu().numpy()
+    ora = oracle.verify_ragged(inputs.logits_to_numpy(batch.target), inputs.logits_to_numpy(batch.draft),
+                               batch.tokens.cpu().numpy(), off, T_used, beta_used, 21, nthreads=NTHREADS)
+    rep = compare(ora, out["accept_len"].cpu().numpy(), out["tokens"].cpu().numpy(),
+                  out["stats"].cpu().numpy(), out["path"].cpu().numpy(), off, None, 1e-5,
+                  batch.tokens.cpu().numpy(), batch.V)
+    assert rep.exempt_decisions == 0 and rep.exempt_tokens == 0
+    # the same through cached statistics (the decisions are then taken by the sampling stage)
+    status.zero_()
+    kw = dict(row_offsets=batch.row_offsets, temperature_per_seq=T, beta_per_seq=beta, seed=21)
+    first = ears.ears_verify_ex(batch.target, batch.draft, batch.tokens, stages=ears.EARS_STAGE_STATS, **kw)
+    late = ears.ears_verify_ex(batch.target, batch.draft, batch.tokens, workspace=first["workspace"],
+                               stages=ears.EARS_STAGE_DECIDE | ears.EARS_STAGE_SAMPLE, status_word=status, **kw)
+    torch.cuda.synchronize()
+    assert int(status.item()) & 8 == 8
+    assert torch.equal(late["accept_len"], out["accept_len"]) and torch.equal(late["tokens"], out["tokens"])
+    # valid parameters leave the bit clear
+    status.zero_()
+    ears.ears_verify_ex(batch.target, batch.draft, batch.tokens, row_offsets=batch.row_offsets,
+                        temperature_per_seq=batch.temperature, beta_per_seq=batch.beta, seed=21,
+                        status_word=status)
+    torch.cuda.synchronize()
+    assert int(status.item()) == 0
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_low_temperature_within_the_documented_range(ears, oracle, dtype):
+    """T = 0.02 with logits of a few units: |logit| / T of several hundred, the upper end of what
+    the sampling stage's fp32 margins are sized for."""
+    from paper_2512_13194_amd import inputs
+    _log("low temperature %s" % dtype)
+    T = 0.02
+    batch = inputs.make_rect(40, 3, 9001, dtype, T=T, data_seed=96, sigma_lo=0.3, sigma_hi=1.5,
+                             draft_noise=0.3, device="cuda")
+    assert float(batch.target.float().abs().max()) / T < 1e3
+    for beta in (0.0, 0.5):
+        rep, ora, _ = run_rect(ears, oracle, batch, T, beta, 22)
+        assert rep.exempt_decisions == 0 and rep.exempt_tokens == 0
+    assert 0 < ora.accept_len.sum() < 40 * 3
+
+
 def test_logit_buffers_larger_than_4_gib(ears, oracle):
     """B = 2500, K = 8, V = 128256, bf16: 5.8 GB of target and 5.1 GB of draft logits (20000
     positions, ten times the headline batch), every output against the oracle."""
