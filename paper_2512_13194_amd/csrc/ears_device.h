@@ -56,6 +56,7 @@ struct Problem {
   int decide_fused;     // where the filter kernel finds the accept length: 0 in accept_len (an earlier
                         // DECIDE stage left it), 1 by scanning the decisions the statistics kernel
                         // left, 2 by deciding each position itself from the cached statistics
+  uint32_t* arrive;     // [B] "last one out" words (see arrive_is_last), zero between calls
   // outputs
   int32_t* accept_len;
   int32_t* out_tokens;
@@ -198,6 +199,43 @@ __device__ __forceinline__ void lds_barrier() {
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
   __builtin_amdgcn_s_barrier();
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
+// ---- last one out ----------------------------------------------------------------------------
+// Workgroups that each finish one part of a piece of work (the chunks of a row) count in on a word
+// in device memory, and the one that completes the count goes on with what needs all the parts.
+// Nobody waits for anybody: every workgroup either leaves or carries on.  The word is zero when
+// the first part arrives: whatever fills a workspace with statistics (the statistics kernel, the
+// import of a producer's statistics) zeroes the words first, and the last to arrive puts the zero
+// back for the next call.
+//
+// What the parts hand over is a few words, and those are written with coherent_store and read
+// with coherent_load (device-scope atomic accesses: they go to the memory side of the caches).
+// A device-scope release fence would order ordinary stores as well, but it writes back the whole
+// L2 of the workgroup's XCD, once per workgroup: measured, that cost more than the launch it was
+// to save.  Here a workgroup only makes sure that its coherent stores have completed (the wait
+// in __syncthreads) before its first thread counts in, and the last one reads after its count
+// has returned; the ordering is that of the instructions, which is what this target guarantees
+// for accesses of device scope.
+//
+// Called by every thread of the workgroup; returns true in all of them or in none.
+__device__ __forceinline__ bool arrive_is_last(uint32_t* word, uint32_t parts, int* sh_flag) {
+  __syncthreads();  // every wave's stores have completed
+  if (threadIdx.x == 0) {
+    const uint32_t before = __hip_atomic_fetch_add(word, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const bool last = before + 1u >= parts;
+    if (last) __hip_atomic_store(word, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    *sh_flag = last ? 1 : 0;
+  }
+  __syncthreads();
+  return *sh_flag != 0;
+}
+
+__device__ __forceinline__ uint32_t coherent_load(const uint32_t* ptr) {
+  return __hip_atomic_load(ptr, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void coherent_store(uint32_t* ptr, uint32_t v) {
+  __hip_atomic_store(ptr, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 // ---- wave64 all-reduce through DPP / swizzle / permlane ---------------------------------------

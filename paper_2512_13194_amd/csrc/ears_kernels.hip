@@ -4,11 +4,12 @@
 //                                       Section 3.3 item 1: max P_t cached, never re-scanned)
 //   stage DECIDE : decide_kernel      - ratio, uniform, tolerance, threshold, three-way decision,
 //                                       first-rejection scan (Section 3.2 steps 2-5, Section 3.1)
-//   stage SAMPLE : sample_kernel      - residual / bonus token by Gumbel-max at slot n: a filter that
-//                  select_kernel        leaves a few survivors per row, then the exact choice (one
-//                  sample_select_kernel launch for both when a row is split into at most two
-//                                       chunks); when DECIDE and SAMPLE run in one call the scan
-//                                       runs in the filter's prologue
+//   stage SAMPLE : sample_select_kernel - residual / bonus token by Gumbel-max at slot n: a filter
+//                  sample_kernel          that leaves a few survivors per row, then the exact choice,
+//                                         in one launch (rows split into more than two chunks: one
+//                                         workgroup per chunk, the last to finish a row chooses);
+//                                         when DECIDE and SAMPLE run in one call the scan runs in
+//                                         the filter's prologue
 //
 // The path is bound by HBM bandwidth (every needed row is read once, plus one re-read of the row
 // pair the sampler needs): no matrix-core work in it.
@@ -42,7 +43,7 @@ namespace ears {
 // Host side.
 // =================================================================================================
 struct WorkspaceLayout {
-  size_t off_Z, off_m, off_lx, off_unc, off_unc_tag, off_decisions, off_records, total;
+  size_t off_Z, off_m, off_lx, off_unc, off_unc_tag, off_decisions, off_records, off_arrive, total;
   int S, chunk;  // how the sampling stage splits a row
 };
 
@@ -77,6 +78,7 @@ static bool workspace_layout(int64_t R, int B, int V, WorkspaceLayout* w) {
   w->off_unc_tag = o;  o = align_up(o + sizeof(uint32_t), 256);
   w->off_decisions = o; o = align_up(o + (size_t)R * sizeof(int32_t), 256);
   w->off_records = o;  o = align_up(o + (size_t)B * S4 * kRecordWords * sizeof(uint32_t), 256);
+  w->off_arrive = o;   o = align_up(o + (size_t)B * sizeof(uint32_t), 256);
   w->total = o;
   w->S = S4;
   w->chunk = chunk;
@@ -115,8 +117,9 @@ static int validate(int dtype, const void* target, const void* draft, const int3
   return EARS_OK;
 }
 
-// The sampling stage: filter and exact choice in one launch when a row is split into one or two
-// chunks, otherwise one launch each.
+// The sampling stage, one launch: filter and exact choice by the same workgroup when a row is
+// split into one or two chunks; otherwise a workgroup per chunk, and the one that finishes a row
+// last chooses.
 template <typename DT, bool kLate>
 static void launch_sample(const Problem& p, hipStream_t stream) {
   if (p.S == 1) {
@@ -129,7 +132,6 @@ static void launch_sample(const Problem& p, hipStream_t stream) {
     // (S * B fits a grid: checked with the other shapes)
     hipLaunchKernelGGL((sample_kernel<DT, kLate>), dim3((unsigned)p.S * (unsigned)p.B), dim3(kBlock), 0,
                        stream, p);
-    hipLaunchKernelGGL((select_kernel<DT>), dim3((unsigned)p.B), dim3(kBlock), 0, stream, p);
   }
 }
 
@@ -289,6 +291,7 @@ int ears_verify_ex(int dtype, const void* target_logits, const void* draft_logit
   p.unc_mode = uncertainty;
   p.decisions = reinterpret_cast<int32_t*>(ws + lay.off_decisions);
   p.records = reinterpret_cast<uint32_t*>(ws + lay.off_records);
+  p.arrive = reinterpret_cast<uint32_t*>(ws + lay.off_arrive);
   p.S = 0;
   p.chunk = 0;
   p.decide_fused = 0;
@@ -577,6 +580,7 @@ int ears_import_stats(int dtype, const void* target_logits, const void* draft_lo
   p.lx = reinterpret_cast<float*>(ws + lay.off_lx);
   p.unc = reinterpret_cast<double*>(ws + lay.off_unc);
   p.unc_tag = reinterpret_cast<uint32_t*>(ws + lay.off_unc_tag);
+  p.arrive = reinterpret_cast<uint32_t*>(ws + lay.off_arrive);
   hipStream_t s = static_cast<hipStream_t>(stream);
   const dim3 grid((unsigned)((total_draft_rows + kBlock - 1) / kBlock));
   if (dtype == EARS_F32)

@@ -336,6 +336,7 @@ __global__ __launch_bounds__(kBlock) void import_stats_kernel(Problem p, const f
                                                                const double* d_sum) {
   const int64_t r = (int64_t)blockIdx.x * kBlock + threadIdx.x;
   if (r >= p.R) return;
+  for (int64_t j = r; j < (int64_t)p.B; j += p.R) p.arrive[j] = 0u;  // as the statistics pass does
   const int b = seq_of_row(p, r);
   const int32_t x = p.tokens[r];
   float lxt = -INFINITY, lxd = -INFINITY;

@@ -157,12 +157,11 @@ __device__ __forceinline__ void row_pass(const typename DT::storage* base, int V
   }
 }
 
+// The work of one workgroup on draft position r (see the head of this file).  sh_m holds
+// kWavesPerBlock floats and sh_s twice as many doubles.
 template <typename DT, int kUnroll, int kMeasure>
-__global__ __launch_bounds__(kBlock) void row_stats_kernel(Problem p) {
+__device__ __forceinline__ void row_stats_body(const Problem& p, int64_t r, float* sh_m, double* sh_s) {
   using storage = typename DT::storage;
-  __shared__ float sh_m[kWavesPerBlock];
-  __shared__ double sh_s[2 * kWavesPerBlock];
-  const int64_t r = (int64_t)blockIdx.x;
   const int b = seq_of_row(p, r);
   const int V = p.V;
   const float c = (float)(kLog2e / (double)seq_temperature(p, b));
@@ -175,6 +174,8 @@ __global__ __launch_bounds__(kBlock) void row_stats_kernel(Problem p) {
   int32_t x = -1;
   double U = 0.0;
   if (threadIdx.x == 0) {
+    // the sampling stage counts from zero (a ragged batch may hold more sequences than positions)
+    for (int64_t j = r; j < (int64_t)p.B; j += p.R) p.arrive[j] = 0u;
     x = p.tokens[r];
     if (x >= 0 && x < V) {
       lxt = DT::load(trow, x);
@@ -209,6 +210,13 @@ __global__ __launch_bounds__(kBlock) void row_stats_kernel(Problem p) {
     p.decisions[r] = decide_position(p, b, r, x, U, (double)Mt, Zt, (double)lxt, (double)Md, Zd,
                                        (double)lxd, unc);
   }
+}
+
+template <typename DT, int kUnroll, int kMeasure>
+__global__ __launch_bounds__(kBlock) void row_stats_kernel(Problem p) {
+  __shared__ float sh_m[kWavesPerBlock];
+  __shared__ double sh_s[2 * kWavesPerBlock];
+  row_stats_body<DT, kUnroll, kMeasure>(p, (int64_t)blockIdx.x, sh_m, sh_s);
 }
 
 // Statistics of the rows of ONE matrix (the target's or the draft's logits on their own): what a

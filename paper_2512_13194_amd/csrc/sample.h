@@ -19,14 +19,14 @@
 //     far) is dropped; the rest (all those with N = 0, one in 256, and a few more) are queued.
 //  2. BOUNDS, queued elements, fp32 with explicit margins: s_lo <= score2 <= s_up.  theta rises
 //     to the largest s_lo; an element survives while s_up >= theta.
-//  3. EXACT (select_kernel, one workgroup per sequence): a lone survivor wins as it stands; several
+//  3. EXACT (select_body, one workgroup per sequence): a lone survivor wins as it stands; several
 //     are scored in fp64 by the definition above as written, argmax with lowest-index ties.
 //
 // Rows the bounds cannot separate (nearly identical target and draft rows, an empty residual,
 // a survivor list that overflows) fall back to an fp64 scan, so the result is always the
-// definition's.  The accept / first-reject scan runs in the filter kernel's prologue (one wave),
-// so a whole verification is three back-to-back launches: row statistics, filter, select; two when
-// a row is split into at most two chunks (sample_select_kernel: filter and select in one).
+// definition's.  The accept / first-reject scan runs in the filter kernel's prologue (one wave) and
+// the exact choice in its epilogue, so a whole verification is two back-to-back launches: row
+// statistics, then filter and choice (one launch for all of it on small batches: one_launch.h).
 #pragma once
 
 #include <type_traits>
@@ -201,8 +201,9 @@ __device__ __forceinline__ int lanes_below(unsigned long long mask) {
 //     threshold of that later moment.
 // Waves publish their thresholds in LDS and pick up the largest at every tile: a lower bound of
 // the best score of any part of the row is one of the whole row's best score.
+// n_out receives the sequence's accept length.
 template <typename DT, int G, bool kLate, bool kFused>
-__device__ __forceinline__ bool sample_body(const Problem& p) {
+__device__ __forceinline__ bool sample_body(const Problem& p, int& n_out) {
   constexpr int kPer = DT::kPerVec;
   constexpr int kVecs = kSampleLaneElems / kPer;  // 16-byte loads per lane and tile
   constexpr int kTile = kSampleTileElems;
@@ -262,6 +263,7 @@ __device__ __forceinline__ bool sample_body(const Problem& p) {
     n = sh_n;
   }
   n = __builtin_amdgcn_readfirstlane(n);
+  n_out = n;
 
   const int64_t r0 = seq_row_begin(p, b);
   const bool residual = n < Kb;
@@ -680,6 +682,12 @@ __device__ __forceinline__ bool sample_body(const Problem& p) {
   // every wave of the workgroup has published its last threshold: this is the workgroup's
   const float theta_wg = ordered_float(sh_theta_row);
   uint32_t* rec0 = p.records + ((size_t)b * p.S + (s - g)) * kRecordWords;  // the first of the G records
+  // records that another workgroup will read (the one that finishes the row last) are written
+  // with coherent stores; those of a workgroup that chooses by itself with ordinary ones
+  auto put = [](uint32_t* ptr, uint32_t v) {
+    if (kFused) *ptr = v;
+    else coherent_store(ptr, v);
+  };
   {
     const bool have = lane < scount;
     const int v = have ? sh_surv_v[wave][lane] : 0;
@@ -693,8 +701,8 @@ __device__ __forceinline__ bool sample_body(const Problem& p) {
       const int slot = base + lanes_below(km);
       if (slot < G * kRecordCap) {
         uint32_t* rec = rec0 + (slot / kRecordCap) * kRecordWords;
-        rec[2 + 2 * (slot % kRecordCap)] = (uint32_t)v;
-        rec[3 + 2 * (slot % kRecordCap)] = __float_as_uint(su);
+        put(rec + 2 + 2 * (slot % kRecordCap), (uint32_t)v);
+        put(rec + 3 + 2 * (slot % kRecordCap), __float_as_uint(su));
       }
       if (kFused) sh_only = v;
     }
@@ -706,9 +714,9 @@ __device__ __forceinline__ bool sample_body(const Problem& p) {
   if (tid == 0) {
     uint32_t* rec = rec0 + g * kRecordWords;
     const int mine = total - g * kRecordCap;
-    rec[0] = __float_as_uint(theta_wg);
-    rec[1] = any_overflow ? (uint32_t)kRecordOverflow
-                          : (uint32_t)(mine < 0 ? 0 : (mine > kRecordCap ? kRecordCap : mine));
+    put(rec, __float_as_uint(theta_wg));
+    put(rec + 1, any_overflow ? (uint32_t)kRecordOverflow
+                              : (uint32_t)(mine < 0 ? 0 : (mine > kRecordCap ? kRecordCap : mine)));
   }
   if (kFused) {
     // exactly one entry of the whole row survived: it is the winner, nothing to compare it with
@@ -721,17 +729,14 @@ __device__ __forceinline__ bool sample_body(const Problem& p) {
   return false;
 }
 
-template <typename DT, bool kLate>
-__global__ __launch_bounds__(kBlock) void sample_kernel(Problem p) {
-  (void)sample_body<DT, 1, kLate, false>(p);
-}
-
 // Level 3.  One workgroup per sequence reads the chunk records of the filter kernel.  A single
 // survivor is the winner as it stands; several are scored in fp64 by the definition; rows the
 // bounds could not separate are scanned in fp64.  In the common case everything this kernel needs
 // (accept length, chunk headers, survivor entries) is requested in one round of loads.
-template <typename DT>
-__device__ __forceinline__ void select_body(const Problem& p, int b) {
+// n is the sequence's accept length.  kCoherent: the records come from other workgroups of the
+// running kernel, which have counted in since (arrive_is_last).
+template <typename DT, bool kCoherent>
+__device__ __forceinline__ void select_body(const Problem& p, int b, int n) {
   using storage = typename DT::storage;
   __shared__ float sh_theta[kWavesPerBlock];
   __shared__ int sh_any_overflow, sh_total, sh_only;
@@ -739,16 +744,16 @@ __device__ __forceinline__ void select_body(const Problem& p, int b) {
   const int V = p.V;
   const uint32_t* recs = p.records + (size_t)b * p.S * kRecordWords;
   const int total = p.S * kRecordCap;
+  auto rd = [](const uint32_t* ptr) -> uint32_t { return kCoherent ? coherent_load(ptr) : *ptr; };
 
   // ---- one round of loads ---------------------------------------------------------------------
-  const int n_raw = p.accept_len[b];
   const int64_t r0 = seq_row_begin(p, b);
   const int Kb = seq_len(p, b);
   float th = kNoThreshold;
   bool ovf = false;
   for (int i = tid; i < p.S; i += kBlock) {
-    th = fmaxf(th, __uint_as_float(recs[(size_t)i * kRecordWords]));
-    ovf = ovf || (int)recs[(size_t)i * kRecordWords + 1] == kRecordOverflow;
+    th = fmaxf(th, __uint_as_float(rd(recs + (size_t)i * kRecordWords)));
+    ovf = ovf || (int)rd(recs + (size_t)i * kRecordWords + 1) == kRecordOverflow;
   }
   // this thread's survivor entry (further entries, for rows split into many chunks, come later)
   int e_cnt = 0, e_j = 0, e_v = -1;
@@ -757,9 +762,9 @@ __device__ __forceinline__ void select_body(const Problem& p, int b) {
     const int i = tid / kRecordCap;
     e_j = tid - i * kRecordCap;
     const uint32_t* rc = recs + (size_t)i * kRecordWords;
-    e_cnt = (int)rc[1];
-    e_v = (int)rc[2 + 2 * e_j];
-    e_s = __uint_as_float(rc[3 + 2 * e_j]);
+    e_cnt = (int)rd(rc + 1);
+    e_v = (int)rd(rc + 2 + 2 * e_j);
+    e_s = __uint_as_float(rd(rc + 3 + 2 * e_j));
   }
   if (tid == 0) { sh_any_overflow = 0; sh_total = 0; sh_only = -1; }
 
@@ -774,7 +779,6 @@ __device__ __forceinline__ void select_body(const Problem& p, int b) {
   for (int w = 1; w < kWavesPerBlock; ++w) theta_g = fmaxf(theta_g, sh_theta[w]);
   const bool any_overflow = sh_any_overflow != 0;
 
-  const int n = n_raw < 0 ? 0 : (n_raw > Kb ? Kb : n_raw);
   const bool residual = n < Kb;
   const bool separable = theta_g > (residual ? kDegenerate : kNoThreshold);
 
@@ -788,7 +792,7 @@ __device__ __forceinline__ void select_body(const Problem& p, int b) {
     for (int idx = tid + kBlock; idx < total; idx += kBlock) {
       const int i = idx / kRecordCap, j = idx - i * kRecordCap;
       const uint32_t* rc = recs + (size_t)i * kRecordWords;
-      if (is_survivor((int)rc[1], j, __uint_as_float(rc[3 + 2 * j]))) { ++mine; my_v = (int)rc[2 + 2 * j]; }
+      if (is_survivor((int)rd(rc + 1), j, __uint_as_float(rd(rc + 3 + 2 * j)))) { ++mine; my_v = (int)rd(rc + 2 + 2 * j); }
     }
     if (mine > 0) { atomicAdd(&sh_total, mine); sh_only = my_v; }
   }
@@ -831,8 +835,8 @@ __device__ __forceinline__ void select_body(const Problem& p, int b) {
     for (int idx = tid; idx < total; idx += kBlock) {
       const int i = idx / kRecordCap, j = idx - i * kRecordCap;
       const uint32_t* rc = recs + (size_t)i * kRecordWords;
-      if (is_survivor((int)rc[1], j, __uint_as_float(rc[3 + 2 * j]))) {
-        const int v = (int)rc[2 + 2 * j];
+      if (is_survivor((int)rd(rc + 1), j, __uint_as_float(rd(rc + 3 + 2 * j)))) {
+        const int v = (int)rd(rc + 2 + 2 * j);
         double sc, lo, hi;
         if (idx == tid && c_v == v) {
           sc = c_s; lo = c_lo; hi = c_hi;
@@ -880,7 +884,7 @@ __device__ __forceinline__ void select_body(const Problem& p, int b) {
     if (separable) {
       score_survivors(false, -1, best, unused);
       for (int i = 0; i < p.S; ++i) {
-        if ((int)recs[(size_t)i * kRecordWords + 1] == kRecordOverflow) {
+        if ((int)rd(recs + (size_t)i * kRecordWords + 1) == kRecordOverflow) {
           const int c0 = i * p.chunk;
           const int c1 = (V - c0) < p.chunk ? V : c0 + p.chunk;
           best = exact_scan<DT>(ctx, c0, c1, mode, best);
@@ -900,9 +904,16 @@ __device__ __forceinline__ void select_body(const Problem& p, int b) {
   if (tid == 0) p.out_tokens[r0 + b + n] = best.v;
 }
 
-template <typename DT>
-__global__ __launch_bounds__(kBlock) void select_kernel(Problem p) {
-  select_body<DT>(p, (int)blockIdx.x);
+// Rows split into more than two chunks: one workgroup per chunk, and the workgroup that finishes a
+// row's last chunk goes on to the exact choice among the records of all of them.
+template <typename DT, bool kLate>
+__global__ __launch_bounds__(kBlock) void sample_kernel(Problem p) {
+  __shared__ int sh_last;
+  int n;
+  (void)sample_body<DT, 1, kLate, false>(p, n);
+  const int b = (int)(blockIdx.x / (unsigned)p.S);
+  if (!arrive_is_last(p.arrive + b, (uint32_t)p.S, &sh_last)) return;
+  select_body<DT, true>(p, b, n);
 }
 
 // Filter and exact choice in one launch, for rows that are split into G <= 2 chunks: a workgroup of
@@ -914,10 +925,11 @@ __global__ __launch_bounds__(kBlock) void select_kernel(Problem p) {
 template <typename DT, int G, bool kLate>
 __global__ __launch_bounds__(kBlock* G, 4)
 void sample_select_kernel(Problem p) {
-  if (sample_body<DT, G, kLate, true>(p)) return;  // uniform over the workgroup
+  int n;
+  if (sample_body<DT, G, kLate, true>(p, n)) return;  // uniform over the workgroup
   __syncthreads();
   if ((int)threadIdx.x >= kBlock) return;  // whole waves
-  select_body<DT>(p, (int)blockIdx.x);
+  select_body<DT, false>(p, (int)blockIdx.x, n);
 }
 
 }  // namespace ears

@@ -134,6 +134,40 @@ def test_edge_shapes(ears, oracle, B, K, V, dtype):
         assert rep.exempt_decisions == 0 and rep.exempt_tokens == 0
 
 
+@pytest.mark.parametrize("B,K,V,dtype,what", [
+    (1, 4, 32000, torch.float32, "four chunks"),
+    (3, 7, 50000, torch.bfloat16, "seven chunks, the last one short"),
+    (64, 8, 32000, torch.bfloat16, "four chunks, many sequences"),
+    (2, 3, 151936, torch.bfloat16, "nineteen chunks"),
+    (5, 2, 140000, torch.float32, "eighteen chunks"),
+    (100, 2, 24577, torch.bfloat16, "four chunks, the last one of a single entry"),
+])
+def test_launch_paths_on_reused_and_uninitialised_workspace(ears, oracle, B, K, V, dtype, what):
+    """Rows of small batches are split into more than two chunks, one workgroup each, and the
+    workgroup that finishes a row last chooses among all their records.  They count in on words of
+    the workspace that are never initialised: the workspace starts as random bytes, then as all
+    ones, is reused by calls of other seeds, and every call must match the oracle."""
+    from paper_2512_13194_amd import inputs
+    batch = inputs.make_rect(B, K, V, dtype, T=0.9, data_seed=4242 + B, draft_noise=0.8, device="cuda")
+    need = ears.ears_workspace_bytes(B * K, B, V)
+    g = torch.Generator(device="cuda").manual_seed(99)
+    ws = torch.randint(0, 256, (need,), dtype=torch.uint8, device="cuda", generator=g)
+    tgt, drf = inputs.logits_to_numpy(batch.target), inputs.logits_to_numpy(batch.draft)
+    tok = batch.tokens.cpu().numpy()
+    T, beta = float(np.float32(0.9)), float(np.float32(0.3))
+    for call, seed in enumerate([11, 12, 11, 13]):
+        if call == 2:
+            ws.fill_(255)
+        _log(f"launch paths: {what}: B={B} K={K} V={V} {dtype} call {call} seed {seed}")
+        out = ears.ears_verify_ex(batch.target, batch.draft, batch.tokens, temperature=0.9, beta=0.3,
+                                  seed=seed, workspace=ws)
+        torch.cuda.synchronize()
+        ora = oracle.verify(tgt, drf, tok, T, beta, seed, nthreads=NTHREADS)
+        rep = compare(ora, out["accept_len"].cpu().numpy(), out["tokens"].cpu().numpy(), None, None,
+                      None, K, RTOL[dtype], tok, V)
+        assert rep.exempt_decisions == 0 and rep.exempt_tokens == 0, rep.line()
+
+
 def test_masked_vocabulary_and_peaked_rows(ears, oracle):
     from paper_2512_13194_amd import inputs
     _log("masked / peaked")
