@@ -74,12 +74,23 @@ __device__ __forceinline__ void accumulate(const float (&f)[N], float c, float& 
   if (kMeasure != kMeasureNone) W += (double)((w[0] + w[1]) + (w[2] + w[3]));
 }
 
+// 2^d for |d| below 1e-3 (here: the rounding error of a product fl(M*c), at most half an ulp of
+// it), to a relative 1e-16: five terms of the series, where the library routine spends several
+// hundred instructions in the one thread every other thread of the workgroup is waiting for.
+__device__ __forceinline__ double exp2_tiny(double d) {
+  const double x = d * 0.69314718055994530942;
+  return 1.0 + x * (1.0 + x * (0.5 + x * (1.0 / 6.0 + x * (1.0 / 24.0))));
+}
+
 // Streams one row; on return thread 0 holds the row maximum M, Z = sum exp((l - M)/T) and in
 // H_out the Shannon entropy (nats) or the total variance of softmax(l/T), whichever kMeasure names.
-template <typename DT, int kUnroll, int kMeasure>
+// `issued` is called once, after the first round of loads has been requested: the place for
+// work whose own loads would otherwise hold up the row's.
+struct NoHook { __device__ __forceinline__ void operator()() const {} };
+template <typename DT, int kUnroll, int kMeasure, typename Hook = NoHook>
 __device__ __forceinline__ void row_pass(const typename DT::storage* base, int V, float c,
                                          float* sh_m, double* sh_s, float& M_out, double& Z_out,
-                                         double& H_out) {
+                                         double& H_out, Hook issued = Hook()) {
   const int tid = (int)threadIdx.x;
   float m_run = -INFINITY, mc = 0.0f;
   double S = 0.0, W = 0.0;
@@ -106,6 +117,7 @@ __device__ __forceinline__ void row_pass(const typename DT::storage* base, int V
       const int i = i0 + u * kBlock;
       raw[u] = i < nvec ? load_stream(vp + i) : DT::neg_inf_vec();
     }
+    if (i0 == tid) issued();
     float f[kUnroll * kPer];
 #pragma unroll
     for (int u = 0; u < kUnroll; ++u) {
@@ -144,7 +156,7 @@ __device__ __forceinline__ void row_pass(const typename DT::storage* base, int V
     for (int w = 0; w < kWavesPerBlock; ++w) Zp += sh_s[w];
     // the lanes used fl(M*c) as the offset; undo its rounding exactly
     const double delta = (double)Mc - (double)M * (double)c;
-    Z_out = Zp * exp2(delta);
+    Z_out = Zp * exp2_tiny(delta);
     M_out = M;
     if (kMeasure != kMeasureNone) {
 #pragma unroll
@@ -168,8 +180,10 @@ __device__ __forceinline__ void row_stats_body(const Problem& p, int64_t r, floa
   const storage* trow = static_cast<const storage*>(p.target) + (r + b) * (int64_t)V;
   const storage* drow = static_cast<const storage*>(p.draft) + r * (int64_t)V;
 
-  // the draft token's two logits are fetched first so that they arrive while the rows stream,
-  // and the position's acceptance uniform is drawn while they do
+  // The draft token's two logits are fetched while the rows stream, and the position's acceptance
+  // uniform is drawn while they do; but only once the first thread's own share of the first row
+  // loads has been requested: fetching the token is a trip to memory, the logits' addresses depend
+  // on it, and a wave that waits for it before its row loads is late for the whole workgroup.
   float lxt = -INFINITY, lxd = -INFINITY;
   int32_t x = -1;
   double U = 0.0;
@@ -177,17 +191,24 @@ __device__ __forceinline__ void row_stats_body(const Problem& p, int64_t r, floa
     // the sampling stage counts from zero (a ragged batch may hold more sequences than positions)
     for (int64_t j = r; j < (int64_t)p.B; j += p.R) p.arrive[j] = 0u;
     x = p.tokens[r];
-    if (x >= 0 && x < V) {
-      lxt = DT::load(trow, x);
-      lxd = DT::load(drow, x);
-    }
-    U = accept_uniform(p.seed, seq_rng_id(p, b), (uint32_t)(r - seq_row_begin(p, b)));
   }
+  bool fetched = false;
+  auto fetch_token_logits = [&]() {
+    fetched = true;
+    if (threadIdx.x == 0) {
+      if (x >= 0 && x < V) {
+        lxt = DT::load(trow, x);
+        lxd = DT::load(drow, x);
+      }
+      U = accept_uniform(p.seed, seq_rng_id(p, b), (uint32_t)(r - seq_row_begin(p, b)));
+    }
+  };
 
   float Mt = 0.0f, Md = 0.0f;
   double Zt = 0.0, Zd = 0.0, Ht = 0.0, Hd = 0.0;
-  row_pass<DT, kUnroll, kMeasure>(trow, V, c, sh_m, sh_s, Mt, Zt, Ht);
+  row_pass<DT, kUnroll, kMeasure>(trow, V, c, sh_m, sh_s, Mt, Zt, Ht, fetch_token_logits);
   row_pass<DT, kUnroll, kMeasureNone>(drow, V, c, sh_m, sh_s, Md, Zd, Hd);
+  if (!fetched) fetch_token_logits();  // a row shorter than one vector has no first round of loads
 
   if (threadIdx.x == 0) {
     p.Z[2 * r] = Zt;
