@@ -51,9 +51,10 @@ static size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 // The sampling stage touches only B rows, so each row is split into S chunks of whole tiles
 // (one tile = 16 vocabulary entries per thread of a workgroup) until about kSampleTargetGroups
-// workgroups exist.  The filter is bound by vector-ALU issue (Philox), so more, shorter
-// workgroups only add their fixed prologue cost.  Filter + select at B = 256, V = 128256 on 256
-// CUs: 31.6 us with 256 groups, 28.6 with 512, 29.5 with 768, 32.6 with 1024, 39 with 2048.
+// workgroups exist.  A workgroup's time is the arrival of its part of the row plus a fixed start
+// and tail, so more, shorter workgroups only add their fixed cost.  Filter + select at B = 256,
+// V = 128256 on 256 CUs: 31.6 us with 256 groups, 28.6 with 512, 29.5 with 768, 32.6 with 1024,
+// 39 with 2048.
 constexpr int kSampleTargetGroups = 512;
 
 static void sample_split(int B, int V, int elems_per_tile, int* S, int* chunk) {

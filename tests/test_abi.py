@@ -239,3 +239,13 @@ def test_row_stats_argument_errors(L):
     assert rs(rows=0) == b.EARS_ERR_SHAPE and rs(V=0) == b.EARS_ERR_SHAPE
     assert rs(T=-1.0) == b.EARS_ERR_PARAM
     assert rs(logits=P + 4) == b.EARS_ERR_ALIGN and rs(rsum=P + 4) == b.EARS_ERR_ALIGN
+
+
+def test_committed_counter_summaries_belong_to_the_current_kernels():
+    """bench.py reports the HBM traffic of the statistics kernel and the instruction count of the
+    sampling kernel from counter runs committed under profiles/, and only while the hash of the
+    kernel sources, the launch code and the build script matches: a change to any of them without
+    new counter runs would silently turn the figures into null."""
+    import bench
+    assert bench.committed_counters(bench.TRAFFIC_FILE) is not None, "regenerate profiles/traffic_row_stats_c2.json"
+    assert bench.committed_counters(bench.FILTER_FILE) is not None, "regenerate profiles/filter_counters_c2.json"
