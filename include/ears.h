@@ -176,7 +176,11 @@ size_t ears_workspace_bytes(int64_t total_draft_rows, int B, int V);
  *                    NULL means 0..B-1.  With explicit ids a sequence's result does not depend
  *                    on its slot in the batch.
  *   workspace        device, >= ears_workspace_bytes(total_draft_rows, B, V) bytes, 256-byte
- *                    aligned; holds the cached row statistics between stages
+ *                    aligned; holds the cached row statistics between stages.  Its contents need
+ *                    no initialisation (the statistics stage and ears_import_stats prepare what
+ *                    the later stages count on); calls that run on one workspace at the same
+ *                    time race.  A call with all three stages is two kernel launches on `stream`
+ *                    and nothing else: no allocation, no copy, no synchronisation
  *   stages           OR of EARS_STAGE_*; DECIDE needs STATS to have run on the same inputs and
  *                    workspace, SAMPLE needs DECIDE (out_accept_len is read back by SAMPLE)
  *   out_stats        optional device [total_draft_rows, EARS_NSTATS] float64 (written by DECIDE)
