@@ -160,7 +160,7 @@ def main() -> int:
 
     # ---- dominant kernel: the row-statistics pass ------------------------------------------------
     # A statistics-stage call launches exactly the kernel instance the whole call starts with
-    # (row_stats_kernel<BF16, 4, 0>: statistics and the per-position decision), and nothing else.
+    # (row_stats_kernel<BF16, 8, 0>: statistics and the per-position decision), and nothing else.
     # Its launches are timed with HIP events on the stream they run on (torch's current stream,
     # which the binding hands to the library): back to back between two events for the average,
     # and one pair of events per launch for the median.
@@ -322,7 +322,7 @@ def main() -> int:
                        "frac_of_hbm_peak_at_median": call_bytes / (call_ms["median_ms"] * 1e-3) / 1e9
                                                      / HBM_PEAK_GBPS},
         "roofline": {"bound": "hbm",
-                     "kernel": "row_stats_kernel<BF16, 4, 0> (statistics + per-position decision: "
+                     "kernel": "row_stats_kernel<BF16, 8, 0> (statistics + per-position decision: "
                                "the instance every call launches)",
                      "achieved": k1_gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": k1_gbps / HBM_PEAK_GBPS,

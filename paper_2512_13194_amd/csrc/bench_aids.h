@@ -10,10 +10,10 @@ namespace ears {
 // =================================================================================================
 constexpr int kBenchBlocks = 4096;
 constexpr size_t kBenchSlabVecs = 16384;  // about 256 KiB per workgroup visit, one logit row
-constexpr int kBenchUnroll = 4;           // 16-byte loads in flight per lane, as in the row pass
+constexpr int kBenchUnroll = 8;           // 16-byte loads in flight per lane, as in the row pass on long rows
 
 // Read-only ceiling: every workgroup streams whole 256 KiB slabs with the same non-temporal
-// 16-byte loads, four in flight per lane, that the row-statistics pass uses, and folds them
+// 16-byte loads, eight in flight per lane, that the row-statistics pass uses, and folds them
 // into a checksum.
 __global__ __launch_bounds__(kBlock) void bench_read_kernel(const uint4* src, size_t nvec,
                                                             size_t slab_vecs, uint32_t* sink) {

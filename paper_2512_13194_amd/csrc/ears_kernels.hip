@@ -56,6 +56,8 @@ static size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 // V = 128256 on 256 CUs: 31.6 us with 256 groups, 28.6 with 512, 29.5 with 768, 32.6 with 1024,
 // 39 with 2048.
 constexpr int kSampleTargetGroups = 512;
+// rows of at least this many bytes take the statistics kernel with eight loads in flight per lane
+constexpr size_t kDeepRowBytes = 128000;
 
 static void sample_split(int B, int V, int elems_per_tile, int* S, int* chunk) {
   const int ntiles = (V + elems_per_tile - 1) / elems_per_tile;
@@ -162,10 +164,18 @@ static int launch(Problem p, int stages, hipStream_t stream) {
       ps.out_stats = nullptr;
       ps.out_path = nullptr;
     }
+    // Long rows run with eight 16-byte loads in flight per lane, short ones with four.  Eight
+    // cost registers (two workgroups fewer per CU) and pay where a launch ends with few groups per
+    // CU left: -2 us of 155 at B = 256, K = 8, V = 128256, +3 % on large batches of 64 KB rows.
+    // The variants with a second running sum have more to compute per element and are better off
+    // with four (entropy: 171 us against 178 us).
+    const bool deep = (size_t)p.V * sizeof(typename DT::storage) >= kDeepRowBytes;
     if (p.unc_mode == EARS_UNCERTAINTY_ENTROPY)
       hipLaunchKernelGGL((row_stats_kernel<DT, 4, kMeasureEntropy>), grid, block, 0, stream, ps);
     else if (p.unc_mode == EARS_UNCERTAINTY_VARIANCE)
       hipLaunchKernelGGL((row_stats_kernel<DT, 4, kMeasureVariance>), grid, block, 0, stream, ps);
+    else if (deep)
+      hipLaunchKernelGGL((row_stats_kernel<DT, 8, kMeasureNone>), grid, block, 0, stream, ps);
     else
       hipLaunchKernelGGL((row_stats_kernel<DT, 4, kMeasureNone>), grid, block, 0, stream, ps);
   }
