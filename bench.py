@@ -29,6 +29,7 @@ TRAFFIC_FILE = os.path.join(ROOT, "profiles", "traffic_row_stats_c2.json")
 FILTER_FILE = os.path.join(ROOT, "profiles", "filter_counters_c2.json")
 KERNEL_SOURCES = ("paper_2512_13194_amd/csrc/row_stats.h", "paper_2512_13194_amd/csrc/ears_device.h",
                   "paper_2512_13194_amd/csrc/decide.h", "paper_2512_13194_amd/csrc/sample.h",
+                  "paper_2512_13194_amd/csrc/verify.h",
                   "paper_2512_13194_amd/csrc/ears_kernels.hip", "paper_2512_13194_amd/build.py")
 
 

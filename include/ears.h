@@ -179,8 +179,12 @@ size_t ears_workspace_bytes(int64_t total_draft_rows, int B, int V);
  *                    aligned; holds the cached row statistics between stages.  Its contents need
  *                    no initialisation (the statistics stage and ears_import_stats prepare what
  *                    the later stages count on); calls that run on one workspace at the same
- *                    time race.  A call with all three stages is two kernel launches on `stream`
- *                    and nothing else: no allocation, no copy, no synchronisation
+ *                    time race.  A call with all three stages is one or two kernel launches on
+ *                    `stream` and nothing else: no allocation, no copy, no synchronisation.
+ *                    (One launch for rectangular batches of long rows with at least 512 draft
+ *                    positions and the MAXPROB measure: its sampling workgroups wait, for a
+ *                    bounded time, for the statistics workgroups of their sequence, which the
+ *                    same launch started before them; see bit 4 of the status word.)
  *   stages           OR of EARS_STAGE_*; DECIDE needs STATS to have run on the same inputs and
  *                    workspace, SAMPLE needs DECIDE (out_accept_len is read back by SAMPLE)
  *   out_stats        optional device [total_draft_rows, EARS_NSTATS] float64 (written by DECIDE)
@@ -197,6 +201,9 @@ size_t ears_workspace_bytes(int64_t total_draft_rows, int B, int V);
  *                            not affected
  *                    bit 3 = a per-sequence temperature was not a positive finite number (1 was
  *                            used) or a per-sequence beta was negative or not finite (0 was used)
+ *                    bit 4 = a sampling workgroup of a single-launch call gave up waiting for
+ *                            its sequence's statistics (more than a tenth of a second; not seen
+ *                            in any run): that sequence's sampled token has not been written
  * ------------------------------------------------------------------------------------------- */
 int ears_verify_ex(int dtype, const void* target_logits, const void* draft_logits,
                    const int32_t* draft_tokens, const int64_t* row_offsets,

@@ -10,7 +10,7 @@ CSRC = os.path.join(_HERE, "csrc")
 LIB = os.path.join(_HERE, "libears.so")
 SOURCES = [os.path.join(CSRC, "ears_kernels.hip")]
 HEADERS = [os.path.join(CSRC, h) for h in ("ears_device.h", "row_stats.h", "decide.h", "sample.h",
-                                            "greedy.h", "lm_head.h", "bench_aids.h")]
+                                            "verify.h", "greedy.h", "lm_head.h", "bench_aids.h")]
 HEADERS.append(os.path.join(os.path.dirname(_HERE), "include", "ears.h"))
 
 HIPCC_FLAGS = [

@@ -105,6 +105,41 @@ __device__ __forceinline__ int first_reject_scan(const Problem& p, int b, int la
   return n;
 }
 
+// The same scan for a workgroup that runs in the SAME launch as the statistics workgroups of its
+// sequence (verify_kernel): one wave polls the positions' ready words until every one carries this
+// call's tag; the decision comes in the word's two lowest bits.  Coherent loads: the writers may
+// sit on another XCD.  The statistics workgroups wait for nobody and are dispatched ahead of
+// any workgroup that waits here (lower workgroup ids), so the wait ends; it is bounded all the
+// same, and a wave that gives up returns -1.
+constexpr int kAwaitPolls = 1 << 17;  // each poll is a trip to memory and a short sleep: > 0.1 s
+__device__ __forceinline__ int await_first_reject(const Problem& p, int b, int lane,
+                                                  bool write_outputs) {
+  const int64_t r0 = seq_row_begin(p, b);
+  const int Kb = seq_len(p, b);
+  int n = Kb;
+  for (int base = 0; base < Kb; base += kWave) {
+    const int i = base + lane;
+    uint32_t word = p.tag | 1u;
+    for (int polls = 0;; ++polls) {
+      if (i < Kb) word = coherent_load(p.ready + r0 + i);
+      if (__ballot((word & ~3u) != p.tag) == 0ull) break;
+      if (polls >= kAwaitPolls) return -1;  // uniform over the wave
+      __builtin_amdgcn_s_sleep(16);
+    }
+    const unsigned long long rejecting = __ballot((word & 3u) == 0u);
+    if (rejecting != 0ull && n == Kb) n = base + (__ffsll((long long)rejecting) - 1);
+  }
+  // what the statistics workgroups stored before their ready words is read after them
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+  if (write_outputs) {
+    if (lane == 0) p.accept_len[b] = n;
+    int32_t* out = p.out_tokens + r0 + b;
+    for (int i = lane; i <= Kb; i += kWave)
+      if (i != n) out[i] = i < n ? p.tokens[r0 + i] : -1;
+  }
+  return n;
+}
+
 // Stand-alone decision stage: kWavesPerBlock sequences per workgroup, one per wave.  Slot n of out_tokens
 // is set to -1 here; the sampling stage overwrites it.
 __global__ __launch_bounds__(kBlock) void decide_kernel(Problem p) {

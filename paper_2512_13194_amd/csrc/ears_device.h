@@ -57,6 +57,9 @@ struct Problem {
                         // DECIDE stage left it), 1 by scanning the decisions the statistics kernel
                         // left, 2 by deciding each position itself from the cached statistics
   uint32_t* arrive;     // [B] "last one out" words (see arrive_is_last), zero between calls
+  uint32_t* ready;      // [R] single-launch calls: ready[r] == tag | decision once position r's
+                        // statistics are in memory (see verify_kernel); zero between calls
+  uint32_t tag;         // this call's value for ready[]: never zero, its two lowest bits clear
   // outputs
   int32_t* accept_len;
   int32_t* out_tokens;
@@ -213,13 +216,21 @@ __device__ __forceinline__ void lds_barrier() {
 // with coherent_load (device-scope atomic accesses: they go to the memory side of the caches).
 // A device-scope release fence would order ordinary stores as well, but it writes back the whole
 // L2 of the workgroup's XCD, once per workgroup: measured, that cost more than the launch it was
-// to save.  Here a workgroup only makes sure that its coherent stores have completed (the wait
-// in __syncthreads) before its first thread counts in, and the last one reads after its count
-// has returned; the ordering is that of the instructions, which is what this target guarantees
-// for accesses of device scope.
-//
+// to save.  Here every wave waits until its own coherent stores have been acknowledged
+// (wait_for_own_stores), the workgroup meets at a barrier, and only then its first thread counts
+// in; the last one reads after its count has returned.
+__device__ __forceinline__ void wait_for_own_stores() {
+  // vmcnt(0): every vector-memory access this wave has issued, stores included, has been
+  // acknowledged.  (A workgroup barrier alone does not wait for them on this target: the waves of
+  // a workgroup share their CU's cache, so the compiler leaves the wait out of the barrier's
+  // workgroup-scope fence.)
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+  __builtin_amdgcn_s_waitcnt(0x0F70);
+}
+
 // Called by every thread of the workgroup; returns true in all of them or in none.
 __device__ __forceinline__ bool arrive_is_last(uint32_t* word, uint32_t parts, int* sh_flag) {
+  wait_for_own_stores();
   __syncthreads();  // every wave's stores have completed
   if (threadIdx.x == 0) {
     const uint32_t before = __hip_atomic_fetch_add(word, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -235,6 +246,24 @@ __device__ __forceinline__ uint32_t coherent_load(const uint32_t* ptr) {
   return __hip_atomic_load(ptr, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 __device__ __forceinline__ void coherent_store(uint32_t* ptr, uint32_t v) {
+  __hip_atomic_store(ptr, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float coherent_load(const float* ptr) {
+  return __hip_atomic_load(ptr, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ double coherent_load(const double* ptr) {
+  return __hip_atomic_load(ptr, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ int32_t coherent_load(const int32_t* ptr) {
+  return __hip_atomic_load(ptr, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void coherent_store(float* ptr, float v) {
+  __hip_atomic_store(ptr, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void coherent_store(double* ptr, double v) {
+  __hip_atomic_store(ptr, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void coherent_store(int32_t* ptr, int32_t v) {
   __hip_atomic_store(ptr, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 

@@ -21,6 +21,7 @@
 #include <hip/hip_runtime.h>
 
 #include <cmath>
+#include <atomic>
 #include <cstdio>
 #include <mutex>
 
@@ -32,6 +33,7 @@
 #include "greedy.h"
 #include "lm_head.h"
 #include "sample.h"
+#include "verify.h"
 
 // Products such as fl(m*c) must stay rounded products (their rounding is undone explicitly
 // later); fused operations are written as fmaf().
@@ -43,7 +45,7 @@ namespace ears {
 // Host side.
 // =================================================================================================
 struct WorkspaceLayout {
-  size_t off_Z, off_m, off_lx, off_unc, off_unc_tag, off_decisions, off_records, off_arrive, total;
+  size_t off_Z, off_m, off_lx, off_unc, off_unc_tag, off_decisions, off_records, off_arrive, off_ready, total;
   int S, chunk;  // how the sampling stage splits a row
 };
 
@@ -58,6 +60,16 @@ static size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 constexpr int kSampleTargetGroups = 512;
 // rows of at least this many bytes take the statistics kernel with eight loads in flight per lane
 constexpr size_t kDeepRowBytes = 128000;
+// A rectangular call with all three stages on long rows runs as ONE launch (verify_kernel) once
+// its statistics workgroups alone fill the chip (two of them per CU at that kernel's register
+// count): the sampling workgroups then take over the CUs as the statistics workgroups run out,
+// instead of starting from an empty chip after a launch gap.  B = 256, K = 8, V = 128256 bf16:
+// 182.6 us against 186.6 us; B = 96: 79 against 89; B = 512, K = 4, V = 151936: 222 against 225.
+// Below, all workgroups are resident from the start and the hand-over through memory costs what
+// the launch gap did (B = 32, K = 8: 41.2 us against 40.9 us); short rows and the measures with a
+// second running sum want more than two statistics workgroups per CU, which the sampling code's
+// registers do not allow in a common kernel (B = 256, K = 8, V = 32000: 67.5 us against 61.3 us).
+constexpr int64_t kSingleLaunchMinRows = 512;
 
 static void sample_split(int B, int V, int elems_per_tile, int* S, int* chunk) {
   const int ntiles = (V + elems_per_tile - 1) / elems_per_tile;
@@ -82,6 +94,7 @@ static bool workspace_layout(int64_t R, int B, int V, WorkspaceLayout* w) {
   w->off_decisions = o; o = align_up(o + (size_t)R * sizeof(int32_t), 256);
   w->off_records = o;  o = align_up(o + (size_t)B * S4 * kRecordWords * sizeof(uint32_t), 256);
   w->off_arrive = o;   o = align_up(o + (size_t)B * sizeof(uint32_t), 256);
+  w->off_ready = o;    o = align_up(o + (size_t)R * sizeof(uint32_t), 256);
   w->total = o;
   w->S = S4;
   w->chunk = chunk;
@@ -153,6 +166,23 @@ static int launch(Problem p, int stages, hipStream_t stream) {
   // DECIDE and SAMPLE on statistics cached earlier: the filter kernel's prologue decides
   const bool late = !stats && decide && sample;
   p.decide_fused = fused ? 1 : (late ? 2 : 0);
+  // Long rows run with eight 16-byte loads in flight per lane, short ones with four.  Eight
+  // cost registers (two workgroups fewer per CU) and pay where a launch ends with few groups per
+  // CU left: -2 us of 155 at B = 256, K = 8, V = 128256, +3 % on large batches of 64 KB rows.
+  // The variants with a second running sum have more to compute per element and are better off
+  // with four (entropy: 171 us against 178 us).
+  const bool deep = (size_t)p.V * sizeof(typename DT::storage) >= kDeepRowBytes;
+  if (fused && p.row_offsets == nullptr && deep && p.unc_mode == EARS_UNCERTAINTY_MAXPROB &&
+      p.R >= kSingleLaunchMinRows && p.R + (int64_t)p.B * (int64_t)p.S <= (int64_t)0x7FFFFFFF) {
+    // One launch: statistics workgroups first, the sampling workgroups behind them (verify.h).
+    // The tag of a call: never zero, its two lowest bits clear, different from call to call.
+    static std::atomic<uint32_t> calls{0};
+    p.tag = ((calls.fetch_add(1u) + 1u) * 2654435761u) & ~3u;
+    if (p.tag == 0u) p.tag = 4u;
+    const dim3 grid((unsigned)(p.R + (int64_t)p.B * (int64_t)p.S)), block(kBlock);
+    hipLaunchKernelGGL((verify_kernel<DT, 8, kMeasureNone>), grid, block, 0, stream, p);
+    return hipGetLastError() == hipSuccess ? EARS_OK : EARS_ERR_HIP;
+  }
   if (stats) {
     const dim3 grid((unsigned)p.R), block(kBlock);
     // The kernel always takes each position's decision as it finishes it.  Only a call that runs
@@ -164,12 +194,6 @@ static int launch(Problem p, int stages, hipStream_t stream) {
       ps.out_stats = nullptr;
       ps.out_path = nullptr;
     }
-    // Long rows run with eight 16-byte loads in flight per lane, short ones with four.  Eight
-    // cost registers (two workgroups fewer per CU) and pay where a launch ends with few groups per
-    // CU left: -2 us of 155 at B = 256, K = 8, V = 128256, +3 % on large batches of 64 KB rows.
-    // The variants with a second running sum have more to compute per element and are better off
-    // with four (entropy: 171 us against 178 us).
-    const bool deep = (size_t)p.V * sizeof(typename DT::storage) >= kDeepRowBytes;
     if (p.unc_mode == EARS_UNCERTAINTY_ENTROPY)
       hipLaunchKernelGGL((row_stats_kernel<DT, 4, kMeasureEntropy>), grid, block, 0, stream, ps);
     else if (p.unc_mode == EARS_UNCERTAINTY_VARIANCE)
@@ -303,6 +327,8 @@ int ears_verify_ex(int dtype, const void* target_logits, const void* draft_logit
   p.decisions = reinterpret_cast<int32_t*>(ws + lay.off_decisions);
   p.records = reinterpret_cast<uint32_t*>(ws + lay.off_records);
   p.arrive = reinterpret_cast<uint32_t*>(ws + lay.off_arrive);
+  p.ready = reinterpret_cast<uint32_t*>(ws + lay.off_ready);
+  p.tag = 0u;
   p.S = 0;
   p.chunk = 0;
   p.decide_fused = 0;
@@ -592,6 +618,8 @@ int ears_import_stats(int dtype, const void* target_logits, const void* draft_lo
   p.unc = reinterpret_cast<double*>(ws + lay.off_unc);
   p.unc_tag = reinterpret_cast<uint32_t*>(ws + lay.off_unc_tag);
   p.arrive = reinterpret_cast<uint32_t*>(ws + lay.off_arrive);
+  p.ready = reinterpret_cast<uint32_t*>(ws + lay.off_ready);
+  p.tag = 0u;
   hipStream_t s = static_cast<hipStream_t>(stream);
   const dim3 grid((unsigned)((total_draft_rows + kBlock - 1) / kBlock));
   if (dtype == EARS_F32)

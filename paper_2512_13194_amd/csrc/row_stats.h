@@ -171,7 +171,10 @@ __device__ __forceinline__ void row_pass(const typename DT::storage* base, int V
 
 // The work of one workgroup on draft position r (see the head of this file).  sh_m holds
 // kWavesPerBlock floats and sh_s twice as many doubles.
-template <typename DT, int kUnroll, int kMeasure>
+// kHand: the position's statistics and decision are handed to workgroups of the SAME launch that
+// wait for them (verify_kernel): they are written with coherent stores, and once those have been
+// acknowledged, ready[r] takes the call's tag.
+template <typename DT, int kUnroll, int kMeasure, bool kHand = false>
 __device__ __forceinline__ void row_stats_body(const Problem& p, int64_t r, float* sh_m, double* sh_s) {
   using storage = typename DT::storage;
   const int b = seq_of_row(p, r);
@@ -189,7 +192,13 @@ __device__ __forceinline__ void row_stats_body(const Problem& p, int64_t r, floa
   double U = 0.0;
   if (threadIdx.x == 0) {
     // the sampling stage counts from zero (a ragged batch may hold more sequences than positions)
-    for (int64_t j = r; j < (int64_t)p.B; j += p.R) p.arrive[j] = 0u;
+    if (kHand) {
+      // rectangular batches only: the sequence's first position zeroes its word, ahead of the tag
+      // that the sequence's sampling workgroups wait for
+      if (r == seq_row_begin(p, b)) coherent_store(p.arrive + b, 0u);
+    } else {
+      for (int64_t j = r; j < (int64_t)p.B; j += p.R) p.arrive[j] = 0u;
+    }
     x = p.tokens[r];
   }
   bool fetched = false;
@@ -211,10 +220,17 @@ __device__ __forceinline__ void row_stats_body(const Problem& p, int64_t r, floa
   if (!fetched) fetch_token_logits();  // a row shorter than one vector has no first round of loads
 
   if (threadIdx.x == 0) {
-    p.Z[2 * r] = Zt;
-    p.Z[2 * r + 1] = Zd;
-    p.m[2 * r] = Mt;
-    p.m[2 * r + 1] = Md;
+    if (kHand) {
+      coherent_store(p.Z + 2 * r, Zt);
+      coherent_store(p.Z + 2 * r + 1, Zd);
+      coherent_store(p.m + 2 * r, Mt);
+      coherent_store(p.m + 2 * r + 1, Md);
+    } else {
+      p.Z[2 * r] = Zt;
+      p.Z[2 * r + 1] = Zd;
+      p.m[2 * r] = Mt;
+      p.m[2 * r + 1] = Md;
+    }
     p.lx[2 * r] = lxt;
     p.lx[2 * r + 1] = lxd;
     // uncertainty of the target distribution: 1 - max P_t = 1 - 1/Z_t, or H / log V, or the
@@ -228,8 +244,13 @@ __device__ __forceinline__ void row_stats_body(const Problem& p, int64_t r, floa
     if (p.status_word && !(Zt > 0.0 && Zt < INFINITY && Zd > 0.0 && Zd < INFINITY))
       atomicOr(p.status_word, 4u);
     if (p.status_word && seq_params_invalid(p, b)) atomicOr(p.status_word, 8u);
-    p.decisions[r] = decide_position(p, b, r, x, U, (double)Mt, Zt, (double)lxt, (double)Md, Zd,
-                                       (double)lxd, unc);
+    const int decision = decide_position(p, b, r, x, U, (double)Mt, Zt, (double)lxt, (double)Md,
+                                         Zd, (double)lxd, unc);
+    p.decisions[r] = decision;
+    if (kHand) {
+      wait_for_own_stores();
+      coherent_store(p.ready + r, p.tag | (uint32_t)decision);
+    }
   }
 }
 

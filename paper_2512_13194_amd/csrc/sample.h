@@ -202,8 +202,12 @@ __device__ __forceinline__ int lanes_below(unsigned long long mask) {
 // Waves publish their thresholds in LDS and pick up the largest at every tile: a lower bound of
 // the best score of any part of the row is one of the whole row's best score.
 // n_out receives the sequence's accept length.
-template <typename DT, int G, bool kLate, bool kFused>
-__device__ __forceinline__ bool sample_body(const Problem& p, int& n_out) {
+// kHand: the statistics and decisions of the sequence come from workgroups of the same launch
+// (verify_kernel): the first wave waits for them, and they are read with coherent loads; n_out is
+// -1, and nothing has been done, if the wait was given up.  `bid` is the workgroup's number among
+// those of the sampling stage.
+template <typename DT, int G, bool kLate, bool kFused, bool kHand = false>
+__device__ __forceinline__ bool sample_body(const Problem& p, int& n_out, unsigned bid) {
   constexpr int kPer = DT::kPerVec;
   constexpr int kVecs = kSampleLaneElems / kPer;  // 16-byte loads per lane and tile
   constexpr int kTile = kSampleTileElems;
@@ -231,8 +235,8 @@ __device__ __forceinline__ bool sample_body(const Problem& p, int& n_out) {
   const int tid = (int)threadIdx.x - g * kBlock, lane = (int)threadIdx.x & (kWave - 1);
   // workgroups are numbered along x: all those of a row one after the other
   const int groups_per_row = kFused ? 1 : p.S;
-  const int b = (int)(blockIdx.x / (unsigned)groups_per_row);
-  const int s = ((int)blockIdx.x - b * groups_per_row) * G + g;
+  const int b = (int)(bid / (unsigned)groups_per_row);
+  const int s = ((int)bid - b * groups_per_row) * G + g;
   const int V = p.V;
 
   // ---- accept length of this sequence ---------------------------------------------------------
@@ -242,7 +246,18 @@ __device__ __forceinline__ bool sample_body(const Problem& p, int& n_out) {
   if (threadIdx.x == 0) sh_theta_row = ordered_int(kNoThreshold);
   if (threadIdx.x < 3) sh_pool_n[threadIdx.x] = 0;
   int n;
-  if (!kLate && p.decide_fused) {
+  if (kHand) {
+    if (wave == 0) {
+      const int nn = await_first_reject(p, b, lane, s == 0);
+      if (lane == 0) sh_n = nn;
+    }
+    lds_barrier();
+    n = sh_n;
+    if (n < 0) {  // uniform over the workgroup
+      n_out = -1;
+      return false;
+    }
+  } else if (!kLate && p.decide_fused) {
     // one decision per position, left by the statistics kernel: every wave scans them for itself
     // (the same few words for all of them), the first wave of the row's first chunk stores the
     // accept length and the accepted prefix
@@ -307,10 +322,17 @@ __device__ __forceinline__ bool sample_body(const Problem& p, int& n_out) {
   const float c = (float)(kLog2e / (double)Tf);
   float mt = 0.0f, kt = 0.0f, md = 0.0f, kd = 0.0f;
   if (residual) {
-    mt = uniform_load(p.m + 2 * r);
-    md = uniform_load(p.m + 2 * r + 1);
-    kt = -__builtin_amdgcn_logf((float)uniform_load(p.Z + 2 * r));
-    kd = -__builtin_amdgcn_logf((float)uniform_load(p.Z + 2 * r + 1));
+    if (kHand) {
+      mt = coherent_load(p.m + 2 * r);
+      md = coherent_load(p.m + 2 * r + 1);
+      kt = -__builtin_amdgcn_logf((float)coherent_load(p.Z + 2 * r));
+      kd = -__builtin_amdgcn_logf((float)coherent_load(p.Z + 2 * r + 1));
+    } else {
+      mt = uniform_load(p.m + 2 * r);
+      md = uniform_load(p.m + 2 * r + 1);
+      kt = -__builtin_amdgcn_logf((float)uniform_load(p.Z + 2 * r));
+      kd = -__builtin_amdgcn_logf((float)uniform_load(p.Z + 2 * r + 1));
+    }
   }
   // level-1 bound, scaled by 2^23: l*cs + ks - bits(float(N)) >= theta * 2^23
   const float cs = c * 0x1p23f;
@@ -734,8 +756,8 @@ __device__ __forceinline__ bool sample_body(const Problem& p, int& n_out) {
 // bounds could not separate are scanned in fp64.  In the common case everything this kernel needs
 // (accept length, chunk headers, survivor entries) is requested in one round of loads.
 // n is the sequence's accept length.  kCoherent: the records come from other workgroups of the
-// running kernel, which have counted in since (arrive_is_last).
-template <typename DT, bool kCoherent>
+// running kernel, which have counted in since (arrive_is_last).  kHand: so do the statistics.
+template <typename DT, bool kCoherent, bool kHand = false>
 __device__ __forceinline__ void select_body(const Problem& p, int b, int n) {
   using storage = typename DT::storage;
   __shared__ float sh_theta[kWavesPerBlock];
@@ -807,10 +829,17 @@ __device__ __forceinline__ void select_body(const Problem& p, int b, int n) {
   SampleCtx ctx;
   ctx.trow = static_cast<const storage*>(p.target) + (r0 + b + n) * (int64_t)V;
   ctx.drow = static_cast<const storage*>(p.draft) + r * (int64_t)V;
-  ctx.mt = residual ? (double)p.m[2 * r] : 0.0;
-  ctx.Zt = residual ? p.Z[2 * r] : 1.0;
-  ctx.md = residual ? (double)p.m[2 * r + 1] : 0.0;
-  ctx.Zd = residual ? p.Z[2 * r + 1] : 1.0;
+  if (kHand) {
+    ctx.mt = residual ? (double)coherent_load(p.m + 2 * r) : 0.0;
+    ctx.Zt = residual ? coherent_load(p.Z + 2 * r) : 1.0;
+    ctx.md = residual ? (double)coherent_load(p.m + 2 * r + 1) : 0.0;
+    ctx.Zd = residual ? coherent_load(p.Z + 2 * r + 1) : 1.0;
+  } else {
+    ctx.mt = residual ? (double)p.m[2 * r] : 0.0;
+    ctx.Zt = residual ? p.Z[2 * r] : 1.0;
+    ctx.md = residual ? (double)p.m[2 * r + 1] : 0.0;
+    ctx.Zd = residual ? p.Z[2 * r + 1] : 1.0;
+  }
   ctx.T = (double)seq_temperature(p, b);
   ctx.seed = p.seed;
   ctx.seq = seq_rng_id(p, b);
@@ -910,7 +939,7 @@ template <typename DT, bool kLate>
 __global__ __launch_bounds__(kBlock) void sample_kernel(Problem p) {
   __shared__ int sh_last;
   int n;
-  (void)sample_body<DT, 1, kLate, false>(p, n);
+  (void)sample_body<DT, 1, kLate, false>(p, n, blockIdx.x);
   const int b = (int)(blockIdx.x / (unsigned)p.S);
   if (!arrive_is_last(p.arrive + b, (uint32_t)p.S, &sh_last)) return;
   select_body<DT, true>(p, b, n);
@@ -926,7 +955,7 @@ template <typename DT, int G, bool kLate>
 __global__ __launch_bounds__(kBlock* G, 4)
 void sample_select_kernel(Problem p) {
   int n;
-  if (sample_body<DT, G, kLate, true>(p, n)) return;  // uniform over the workgroup
+  if (sample_body<DT, G, kLate, true>(p, n, blockIdx.x)) return;  // uniform over the workgroup
   __syncthreads();
   if ((int)threadIdx.x >= kBlock) return;  // whole waves
   select_body<DT, false>(p, (int)blockIdx.x, n);

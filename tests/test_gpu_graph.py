@@ -14,12 +14,16 @@ pytestmark = pytest.mark.gpu
 NTHREADS = min(16, os.cpu_count() or 1)
 
 
-def test_captured_call_replays_like_eager_and_like_the_oracle(oracle):
+@pytest.mark.parametrize("B,K,V", [
+    (64, 5, 32000),    # two launches: statistics, then sampling
+    (72, 8, 64000),    # long rows, 576 positions: the whole call is one launch
+])
+def test_captured_call_replays_like_eager_and_like_the_oracle(oracle, B, K, V):
     import paper_2512_13194_amd as ears
     from paper_2512_13194_amd import inputs
     ears.lib()
-    print("graph capture", flush=True)
-    B, K, V, T, beta, seed = 64, 5, 32000, 0.8, 0.5, 77
+    print("graph capture B=%d K=%d V=%d" % (B, K, V), flush=True)
+    T, beta, seed = 0.8, 0.5, 77
     batch = inputs.make_rect(B, K, V, torch.bfloat16, T=T, data_seed=1001, draft_noise=0.5, device="cuda")
     ids = torch.arange(B, dtype=torch.int64, device="cuda")
     ws = torch.empty(ears.ears_workspace_bytes(B * K, B, V), dtype=torch.uint8, device="cuda")

@@ -141,12 +141,17 @@ def test_edge_shapes(ears, oracle, B, K, V, dtype):
     (2, 3, 151936, torch.bfloat16, "nineteen chunks"),
     (5, 2, 140000, torch.float32, "eighteen chunks"),
     (100, 2, 24577, torch.bfloat16, "four chunks, the last one of a single entry"),
+    (72, 8, 64000, torch.bfloat16, "one launch for the whole call, eight chunks"),
+    (520, 1, 64000, torch.bfloat16, "one launch, one position and one chunk per sequence"),
+    (130, 4, 32000, torch.float32, "one launch, fp32, four chunks"),
 ])
 def test_launch_paths_on_reused_and_uninitialised_workspace(ears, oracle, B, K, V, dtype, what):
     """Rows of small batches are split into more than two chunks, one workgroup each, and the
     workgroup that finishes a row last chooses among all their records.  They count in on words of
     the workspace that are never initialised: the workspace starts as random bytes, then as all
-    ones, is reused by calls of other seeds, and every call must match the oracle."""
+    ones, is reused by calls of other seeds, and every call must match the oracle.  The same for
+    calls that run as ONE launch (long rows, at least 512 draft positions), whose sampling
+    workgroups wait on tagged words of the workspace."""
     from paper_2512_13194_amd import inputs
     batch = inputs.make_rect(B, K, V, dtype, T=0.9, data_seed=4242 + B, draft_noise=0.8, device="cuda")
     need = ears.ears_workspace_bytes(B * K, B, V)
@@ -166,6 +171,39 @@ def test_launch_paths_on_reused_and_uninitialised_workspace(ears, oracle, B, K, 
         rep = compare(ora, out["accept_len"].cpu().numpy(), out["tokens"].cpu().numpy(), None, None,
                       None, K, RTOL[dtype], tok, V)
         assert rep.exempt_decisions == 0 and rep.exempt_tokens == 0, rep.line()
+
+
+def test_single_launch_call_equals_staged_calls(ears, oracle):
+    """A rectangular call on long rows with at least 512 draft positions runs as one launch; the
+    same problem through separate stage calls (STATS, then DECIDE | SAMPLE; and STATS | DECIDE,
+    then SAMPLE) runs the statistics and sampling kernels on their own.  All three give the
+    oracle's result; the status word stays clear."""
+    from paper_2512_13194_amd import inputs
+    B, K, V = 80, 7, 70001  # rows that are not 16-byte multiples
+    batch = inputs.make_rect(B, K, V, torch.bfloat16, T=1.1, data_seed=31337, draft_noise=0.7, device="cuda")
+    kw = dict(temperature=1.1, beta=0.4, seed=2024)
+    _log("single launch against staged calls")
+    status = torch.zeros(1, dtype=torch.int32, device="cuda")
+    one = ears.ears_verify_ex(batch.target, batch.draft, batch.tokens, status_word=status, **kw)
+    a = ears.ears_verify_ex(batch.target, batch.draft, batch.tokens, stages=ears.EARS_STAGE_STATS, **kw)
+    late = ears.ears_verify_ex(batch.target, batch.draft, batch.tokens, workspace=a["workspace"],
+                               stages=ears.EARS_STAGE_DECIDE | ears.EARS_STAGE_SAMPLE, **kw)
+    c = ears.ears_verify_ex(batch.target, batch.draft, batch.tokens,
+                            stages=ears.EARS_STAGE_STATS | ears.EARS_STAGE_DECIDE, **kw)
+    split = ears.ears_verify_ex(batch.target, batch.draft, batch.tokens, workspace=c["workspace"],
+                                stages=ears.EARS_STAGE_SAMPLE, out_accept_len=c["accept_len"],
+                                out_tokens=c["tokens"], **kw)
+    torch.cuda.synchronize()
+    assert int(status.item()) == 0
+    for other in (late, split):
+        assert torch.equal(one["accept_len"], other["accept_len"])
+        assert torch.equal(one["tokens"], other["tokens"])
+    tok = batch.tokens.cpu().numpy()
+    ora = oracle.verify(inputs.logits_to_numpy(batch.target), inputs.logits_to_numpy(batch.draft), tok,
+                        float(np.float32(1.1)), float(np.float32(0.4)), 2024, nthreads=NTHREADS)
+    rep = compare(ora, one["accept_len"].cpu().numpy(), one["tokens"].cpu().numpy(), None, None,
+                  None, K, RTOL[torch.bfloat16], tok, V)
+    assert rep.exempt_decisions == 0 and rep.exempt_tokens == 0, rep.line()
 
 
 def test_masked_vocabulary_and_peaked_rows(ears, oracle):
