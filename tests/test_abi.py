@@ -247,5 +247,5 @@ def test_committed_counter_summaries_belong_to_the_current_kernels():
     kernel sources, the launch code and the build script matches: a change to any of them without
     new counter runs would silently turn the figures into null."""
     import bench
-    assert bench.committed_counters(bench.TRAFFIC_FILE) is not None, "regenerate profiles/traffic_row_stats_c2.json"
+    assert bench.committed_counters(bench.TRAFFIC_FILE) is not None, "regenerate profiles/traffic_verify_c2.json"
     assert bench.committed_counters(bench.FILTER_FILE) is not None, "regenerate profiles/filter_counters_c2.json"
