@@ -326,6 +326,14 @@ void ears_release(void);
  *   ears_bench_copy: dst[0..bytes) = src[0..bytes), both 16-byte aligned, bytes multiple of 16
  * ------------------------------------------------------------------------------------------- */
 int ears_bench_read_sink_words(void);
+/* Test aid for the single-launch form of a whole call (see `workspace` of ears_verify_ex), process-
+ * wide, not for production use: `force` != 0 makes every eligible call (rectangular, long rows,
+ * MAXPROB, all three stages) take the single launch whatever its number of draft positions;
+ * `wait_polls` >= 0 replaces the number of polls after which a waiting sampling workgroup gives
+ * up and raises bit 4 of the status word (0: after its first look), negative restores the
+ * default.  ears_test_single_launch(0, -1) restores normal operation.  With it a test can see the
+ * give-up path end normally, every kernel exiting, without anything having gone wrong. */
+void ears_test_single_launch(int force, int wait_polls);
 int ears_bench_read(const void* src, size_t bytes, uint32_t* sink, void* stream);
 int ears_bench_copy(void* dst, const void* src, size_t bytes, void* stream);
 

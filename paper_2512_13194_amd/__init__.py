@@ -22,6 +22,7 @@ from .binding import (  # noqa: F401
     EarsError,
     ears_bench_copy,
     ears_bench_read,
+    ears_test_single_launch,
     ears_greedy_workspace_bytes,
     ears_import_stats,
     ears_lm_head_bf16,

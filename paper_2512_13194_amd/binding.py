@@ -77,6 +77,8 @@ def lib() -> ctypes.CDLL:
         L.ears_import_stats.restype = i32
         L.ears_release.argtypes = []
         L.ears_release.restype = None
+        L.ears_test_single_launch.argtypes = [i32, i32]
+        L.ears_test_single_launch.restype = None
         L.ears_bench_read_sink_words.argtypes = []
         L.ears_bench_read_sink_words.restype = i32
         L.ears_bench_read.argtypes = [vp, sz, vp, vp]
@@ -399,6 +401,10 @@ def ears_import_stats(target_logits, draft_logits, draft_tokens, target_row_max,
 
 def ears_release() -> None:
     lib().ears_release()
+
+
+def ears_test_single_launch(force: bool, wait_polls: int = -1) -> None:
+    lib().ears_test_single_launch(1 if force else 0, int(wait_polls))
 
 
 def ears_bench_read(src: torch.Tensor, sink: Optional[torch.Tensor] = None, stream=None):

@@ -111,7 +111,8 @@ __device__ __forceinline__ int first_reject_scan(const Problem& p, int b, int la
 // sit on another XCD.  The statistics workgroups wait for nobody and are dispatched ahead of
 // any workgroup that waits here (lower workgroup ids), so the wait ends; it is bounded all the
 // same, and a wave that gives up returns -1.
-constexpr int kAwaitPolls = 1 << 17;  // each poll is a trip to memory and a short sleep: > 0.1 s
+constexpr int kAwaitPolls = 1 << 17;  // the default of Problem::await_polls; each poll is a trip to
+                                      // memory and a short sleep: > 0.1 s
 __device__ __forceinline__ int await_first_reject(const Problem& p, int b, int lane,
                                                   bool write_outputs) {
   const int64_t r0 = seq_row_begin(p, b);
@@ -123,7 +124,7 @@ __device__ __forceinline__ int await_first_reject(const Problem& p, int b, int l
     for (int polls = 0;; ++polls) {
       if (i < Kb) word = coherent_load(p.ready + r0 + i);
       if (__ballot((word & ~3u) != p.tag) == 0ull) break;
-      if (polls >= kAwaitPolls) return -1;  // uniform over the wave
+      if (polls >= p.await_polls) return -1;  // uniform over the wave
       __builtin_amdgcn_s_sleep(16);
     }
     const unsigned long long rejecting = __ballot((word & 3u) == 0u);

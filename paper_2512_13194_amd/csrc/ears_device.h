@@ -60,6 +60,7 @@ struct Problem {
   uint32_t* ready;      // [R] single-launch calls: ready[r] == tag | decision once position r's
                         // statistics are in memory (see verify_kernel); zero between calls
   uint32_t tag;         // this call's value for ready[]: never zero, its two lowest bits clear
+  int await_polls;      // how often a sampling workgroup of a single-launch call polls before it gives up
   // outputs
   int32_t* accept_len;
   int32_t* out_tokens;

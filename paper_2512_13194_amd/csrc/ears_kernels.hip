@@ -70,6 +70,10 @@ constexpr size_t kDeepRowBytes = 128000;
 // second running sum want more than two statistics workgroups per CU, which the sampling code's
 // registers do not allow in a common kernel (B = 256, K = 8, V = 32000: 67.5 us against 61.3 us).
 constexpr int64_t kSingleLaunchMinRows = 512;
+// test aid (ears_test_single_launch): take the single launch below that size too, and the number
+// of polls after which a waiting workgroup gives up
+static std::atomic<int> g_force_single_launch{0};
+static std::atomic<int> g_await_polls{kAwaitPolls};
 
 static void sample_split(int B, int V, int elems_per_tile, int* S, int* chunk) {
   const int ntiles = (V + elems_per_tile - 1) / elems_per_tile;
@@ -173,12 +177,14 @@ static int launch(Problem p, int stages, hipStream_t stream) {
   // with four (entropy: 171 us against 178 us).
   const bool deep = (size_t)p.V * sizeof(typename DT::storage) >= kDeepRowBytes;
   if (fused && p.row_offsets == nullptr && deep && p.unc_mode == EARS_UNCERTAINTY_MAXPROB &&
-      p.R >= kSingleLaunchMinRows && p.R + (int64_t)p.B * (int64_t)p.S <= (int64_t)0x7FFFFFFF) {
+      (p.R >= kSingleLaunchMinRows || g_force_single_launch.load() != 0) &&
+      p.R + (int64_t)p.B * (int64_t)p.S <= (int64_t)0x7FFFFFFF) {
     // One launch: statistics workgroups first, the sampling workgroups behind them (verify.h).
     // The tag of a call: never zero, its two lowest bits clear, different from call to call.
     static std::atomic<uint32_t> calls{0};
     p.tag = ((calls.fetch_add(1u) + 1u) * 2654435761u) & ~3u;
     if (p.tag == 0u) p.tag = 4u;
+    p.await_polls = g_await_polls.load();
     const dim3 grid((unsigned)(p.R + (int64_t)p.B * (int64_t)p.S)), block(kBlock);
     hipLaunchKernelGGL((verify_kernel<DT, 8, kMeasureNone>), grid, block, 0, stream, p);
     return hipGetLastError() == hipSuccess ? EARS_OK : EARS_ERR_HIP;
@@ -329,6 +335,7 @@ int ears_verify_ex(int dtype, const void* target_logits, const void* draft_logit
   p.arrive = reinterpret_cast<uint32_t*>(ws + lay.off_arrive);
   p.ready = reinterpret_cast<uint32_t*>(ws + lay.off_ready);
   p.tag = 0u;
+  p.await_polls = kAwaitPolls;
   p.S = 0;
   p.chunk = 0;
   p.decide_fused = 0;
@@ -620,6 +627,7 @@ int ears_import_stats(int dtype, const void* target_logits, const void* draft_lo
   p.arrive = reinterpret_cast<uint32_t*>(ws + lay.off_arrive);
   p.ready = reinterpret_cast<uint32_t*>(ws + lay.off_ready);
   p.tag = 0u;
+  p.await_polls = kAwaitPolls;
   hipStream_t s = static_cast<hipStream_t>(stream);
   const dim3 grid((unsigned)((total_draft_rows + kBlock - 1) / kBlock));
   if (dtype == EARS_F32)
@@ -629,6 +637,11 @@ int ears_import_stats(int dtype, const void* target_logits, const void* draft_lo
     hipLaunchKernelGGL(import_stats_kernel<BF16>, grid, dim3(kBlock), 0, s, p, target_row_max,
                        target_row_sumexp, target_row_entropy, draft_row_max, draft_row_sumexp);
   return hipGetLastError() == hipSuccess ? EARS_OK : EARS_ERR_HIP;
+}
+
+void ears_test_single_launch(int force, int wait_polls) {
+  g_force_single_launch.store(force != 0 ? 1 : 0);
+  g_await_polls.store(wait_polls >= 0 ? wait_polls : kAwaitPolls);
 }
 
 int ears_bench_read_sink_words(void) { return kBenchBlocks; }

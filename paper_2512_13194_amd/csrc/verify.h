@@ -27,7 +27,10 @@ namespace ears {
 // out; those of sequences that finished long ago never wait, only those of the last sequences
 // do, briefly.  (Placing the sampling workgroups of a sequence earlier among the ids, a fixed
 // number of sequences behind its statistics workgroups, so that they run beside the stream rather
-// than at its end, lost all of the gain: 185.7 us against 182.2 us at B = 256, K = 8, V = 128256.)
+// than at its end, lost all of the gain: 185.7 us against 182.2 us at B = 256, K = 8, V = 128256.
+// Splitting the rows of the last sequences, whose sampling workgroups run as the chip empties,
+// into more and shorter chunks than the others gained nothing either: 181-182 us whether those 64
+// rows were cut in two or in four, 185-186 us in eight.)
 //
 // The ready words are zero between calls: the workgroup that finishes a row last clears those of
 // its sequence (every waiter of the sequence has counted in by then).  The tag differs from call

@@ -206,6 +206,43 @@ def test_single_launch_call_equals_staged_calls(ears, oracle):
     assert rep.exempt_decisions == 0 and rep.exempt_tokens == 0, rep.line()
 
 
+def test_single_launch_wait_is_bounded_and_small_batches_work_through_it(ears, oracle):
+    """The sampling workgroups of a single-launch call wait for the statistics workgroups of their
+    sequence, for a bounded number of polls.  With the bound set to zero from the host and a batch
+    small enough for every workgroup to start at once, they look once, find nothing (the
+    statistics of a row take microseconds), give up and raise bit 4 of the status word: every
+    kernel ends normally.  With the bound restored the same small batch, still forced through the
+    single launch, gives the oracle's result, also right after the abandoned call on the same
+    workspace."""
+    from paper_2512_13194_amd import inputs
+    B, K, V = 8, 2, 64000
+    batch = inputs.make_rect(B, K, V, torch.bfloat16, T=1.0, data_seed=606, draft_noise=0.6, device="cuda")
+    ws = torch.zeros(ears.ears_workspace_bytes(B * K, B, V), dtype=torch.uint8, device="cuda")
+    status = torch.zeros(1, dtype=torch.int32, device="cuda")
+    kw = dict(temperature=1.0, beta=0.3, workspace=ws, status_word=status)
+    tok = batch.tokens.cpu().numpy()
+    tgt, drf = inputs.logits_to_numpy(batch.target), inputs.logits_to_numpy(batch.draft)
+    try:
+        _log("single launch: wait bound 0")
+        ears.ears_test_single_launch(True, 0)
+        ears.ears_verify_ex(batch.target, batch.draft, batch.tokens, seed=1, **kw)
+        torch.cuda.synchronize()
+        assert int(status.item()) & 16 == 16
+        status.zero_()
+        ears.ears_test_single_launch(True, -1)
+        for seed in (2, 3):
+            _log("single launch forced on a small batch, seed %d" % seed)
+            out = ears.ears_verify_ex(batch.target, batch.draft, batch.tokens, seed=seed, **kw)
+            torch.cuda.synchronize()
+            assert int(status.item()) == 0
+            ora = oracle.verify(tgt, drf, tok, 1.0, float(np.float32(0.3)), seed, nthreads=NTHREADS)
+            rep = compare(ora, out["accept_len"].cpu().numpy(), out["tokens"].cpu().numpy(), None, None,
+                          None, K, RTOL[torch.bfloat16], tok, V)
+            assert rep.exempt_decisions == 0 and rep.exempt_tokens == 0, rep.line()
+    finally:
+        ears.ears_test_single_launch(False, -1)
+
+
 def test_masked_vocabulary_and_peaked_rows(ears, oracle):
     from paper_2512_13194_amd import inputs
     _log("masked / peaked")
