@@ -42,8 +42,9 @@ def _both(ears, batch, T, beta, seed, uncertainty=0, ragged=False):
 
 def test_no_alloc_matches_workspace_entry_point(ears):
     from paper_2512_13194_amd import inputs
-    print("no-alloc: B=96 K=6 V=50257, then B=5 K=2 V=1003, then ragged", flush=True)
-    big = inputs.make_rect(96, 6, 50257, torch.bfloat16, T=0.9, data_seed=501, draft_noise=1.0, device="cuda")
+    print("no-alloc: B=96 K=6 V=65536, then B=5 K=2 V=1003, then ragged", flush=True)
+    # long rows, 576 draft positions: this call is a single launch, the small one after it two
+    big = inputs.make_rect(96, 6, 65536, torch.bfloat16, T=0.9, data_seed=501, draft_noise=1.0, device="cuda")
     small = inputs.make_rect(5, 2, 1003, torch.float32, T=1.1, data_seed=502, device="cuda")
     acc_big, _ = _both(ears, big, 0.9, 0.3, 41)
     acc_small, _ = _both(ears, small, 1.1, 0.6, 42, uncertainty=ears.EARS_UNCERTAINTY_ENTROPY)
