@@ -182,7 +182,7 @@ size_t ears_workspace_bytes(int64_t total_draft_rows, int B, int V);
  *                    time race.  A call with all three stages is one or two kernel launches on
  *                    `stream` and nothing else: no allocation, no copy, no synchronisation.
  *                    (One launch for rectangular batches of long rows with at least 512 draft
- *                    positions and the MAXPROB measure: its sampling workgroups wait, for a
+ *                    positions: its sampling workgroups wait, for a
  *                    bounded time, for the statistics workgroups of their sequence, which the
  *                    same launch started before them; see bit 4 of the status word.)
  *   stages           OR of EARS_STAGE_*; DECIDE needs STATS to have run on the same inputs and
@@ -328,7 +328,7 @@ void ears_release(void);
 int ears_bench_read_sink_words(void);
 /* Test aid for the single-launch form of a whole call (see `workspace` of ears_verify_ex), process-
  * wide, not for production use: `force` != 0 makes every eligible call (rectangular, long rows,
- * MAXPROB, all three stages) take the single launch whatever its number of draft positions;
+ * all three stages) take the single launch whatever its number of draft positions;
  * `wait_polls` >= 0 replaces the number of polls after which a waiting sampling workgroup gives
  * up and raises bit 4 of the status word (0: after its first look), negative restores the
  * default.  ears_test_single_launch(0, -1) restores normal operation.  With it a test can see the

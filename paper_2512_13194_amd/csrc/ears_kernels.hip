@@ -66,9 +66,10 @@ constexpr size_t kDeepRowBytes = 128000;
 // instead of starting from an empty chip after a launch gap.  B = 256, K = 8, V = 128256 bf16:
 // 182.6 us against 186.6 us; B = 96: 79 against 89; B = 512, K = 4, V = 151936: 222 against 225.
 // Below, all workgroups are resident from the start and the hand-over through memory costs what
-// the launch gap did (B = 32, K = 8: 41.2 us against 40.9 us); short rows and the measures with a
-// second running sum want more than two statistics workgroups per CU, which the sampling code's
-// registers do not allow in a common kernel (B = 256, K = 8, V = 32000: 67.5 us against 61.3 us).
+// the launch gap did (B = 32, K = 8: 41.2 us against 40.9 us); short rows want more than two
+// statistics workgroups per CU, which the sampling code's registers do not allow in a common
+// kernel (B = 256, K = 8, V = 32000: 67.5 us against 61.3 us).  With the entropy and variance
+// measures the same headline batch takes 181 and 177 us against 185 and 183 us.
 constexpr int64_t kSingleLaunchMinRows = 512;
 // test aid (ears_test_single_launch): take the single launch below that size too, and the number
 // of polls after which a waiting workgroup gives up
@@ -176,7 +177,7 @@ static int launch(Problem p, int stages, hipStream_t stream) {
   // The variants with a second running sum have more to compute per element and are better off
   // with four (entropy: 171 us against 178 us).
   const bool deep = (size_t)p.V * sizeof(typename DT::storage) >= kDeepRowBytes;
-  if (fused && p.row_offsets == nullptr && deep && p.unc_mode == EARS_UNCERTAINTY_MAXPROB &&
+  if (fused && p.row_offsets == nullptr && deep &&
       (p.R >= kSingleLaunchMinRows || g_force_single_launch.load() != 0) &&
       p.R + (int64_t)p.B * (int64_t)p.S <= (int64_t)0x7FFFFFFF) {
     // One launch: statistics workgroups first, the sampling workgroups behind them (verify.h).
@@ -186,7 +187,14 @@ static int launch(Problem p, int stages, hipStream_t stream) {
     if (p.tag == 0u) p.tag = 4u;
     p.await_polls = g_await_polls.load();
     const dim3 grid((unsigned)(p.R + (int64_t)p.B * (int64_t)p.S)), block(kBlock);
-    hipLaunchKernelGGL((verify_kernel<DT, 8, kMeasureNone>), grid, block, 0, stream, p);
+    // (eight loads in flight for every measure: the kernel runs two workgroups per CU whatever the
+    // statistics code needs, and with two, four loads in flight are no better for the entropy)
+    if (p.unc_mode == EARS_UNCERTAINTY_ENTROPY)
+      hipLaunchKernelGGL((verify_kernel<DT, 8, kMeasureEntropy>), grid, block, 0, stream, p);
+    else if (p.unc_mode == EARS_UNCERTAINTY_VARIANCE)
+      hipLaunchKernelGGL((verify_kernel<DT, 8, kMeasureVariance>), grid, block, 0, stream, p);
+    else
+      hipLaunchKernelGGL((verify_kernel<DT, 8, kMeasureNone>), grid, block, 0, stream, p);
     return hipGetLastError() == hipSuccess ? EARS_OK : EARS_ERR_HIP;
   }
   if (stats) {
