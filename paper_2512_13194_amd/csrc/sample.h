@@ -319,14 +319,19 @@ __device__ __forceinline__ bool sample_body(const Problem& p, int& n_out, unsign
   // fp32 constants of levels 1 and 2.  The cached statistics are the same words for every lane:
   // read through the constant address space they are scalar loads, which leave the vector-memory
   // counter to the tile loads that follow.
+  // (kHand: they come from workgroups of the running launch and are vector loads of device scope;
+  // they are requested here and first looked at, in take_statistics, once the first tile's loads
+  // have been requested behind them, so that the two trips to memory are one.)
   const float c = (float)(kLog2e / (double)Tf);
   float mt = 0.0f, kt = 0.0f, md = 0.0f, kd = 0.0f;
+  float hand_mt = 0.0f, hand_md = 0.0f;
+  double hand_Zt = 1.0, hand_Zd = 1.0;
   if (residual) {
     if (kHand) {
-      mt = coherent_load(p.m + 2 * r);
-      md = coherent_load(p.m + 2 * r + 1);
-      kt = -__builtin_amdgcn_logf((float)coherent_load(p.Z + 2 * r));
-      kd = -__builtin_amdgcn_logf((float)coherent_load(p.Z + 2 * r + 1));
+      hand_mt = coherent_load(p.m + 2 * r);
+      hand_md = coherent_load(p.m + 2 * r + 1);
+      hand_Zt = coherent_load(p.Z + 2 * r);
+      hand_Zd = coherent_load(p.Z + 2 * r + 1);
     } else {
       mt = uniform_load(p.m + 2 * r);
       md = uniform_load(p.m + 2 * r + 1);
@@ -336,7 +341,19 @@ __device__ __forceinline__ bool sample_body(const Problem& p, int& n_out, unsign
   }
   // level-1 bound, scaled by 2^23: l*cs + ks - bits(float(N)) >= theta * 2^23
   const float cs = c * 0x1p23f;
-  const float ks = (float)(((double)kt + 135.0 + (double)kTestMargin - (double)mt * (double)c) * 0x1p23);
+  float ks = (float)(((double)kt + 135.0 + (double)kTestMargin - (double)mt * (double)c) * 0x1p23);
+  auto take_statistics = [&]() {
+    if (kHand && residual) {
+      // keeps the compiler from looking at the loaded values (and waiting for them) any earlier
+      __builtin_amdgcn_sched_barrier(0);
+      asm volatile("" : "+v"(hand_mt), "+v"(hand_md), "+v"(hand_Zt), "+v"(hand_Zd));
+      mt = hand_mt;
+      md = hand_md;
+      kt = -__builtin_amdgcn_logf((float)hand_Zt);
+      kd = -__builtin_amdgcn_logf((float)hand_Zd);
+      ks = (float)(((double)kt + 135.0 + (double)kTestMargin - (double)mt * (double)c) * 0x1p23);
+    }
+  };
 
   float theta = kNoThreshold;  // wave-uniform: best proven lower bound of the maximum score (log2)
   int qcount = 0;            // wave-uniform: queued candidates
@@ -585,6 +602,7 @@ __device__ __forceinline__ bool sample_body(const Problem& p, int& n_out, unsign
     static_assert(kDepth == 4 || kDepth == 2, "tile buffers");
     uint4 raw0[kVecs], raw1[kVecs], raw2[kVecs], raw3[kVecs];
     load_tile(raw0, v_begin);
+    take_statistics();
 
     // One tile, first half: `raw` holds this lane's entries of the tile that starts at tile0 and is
     // refilled with those of the tile kDepth further on.  Leaves the entries with coarse byte 255
