@@ -602,6 +602,16 @@ __device__ __forceinline__ bool sample_body(const Problem& p, int& n_out, unsign
     static_assert(kDepth == 4 || kDepth == 2, "tile buffers");
     uint4 raw0[kVecs], raw1[kVecs], raw2[kVecs], raw3[kVecs];
     load_tile(raw0, v_begin);
+    // kHand: the workgroup starts on a chip that is running empty, not beside every other
+    // workgroup of its kind: nothing is gained by holding the next tiles back until the first has
+    // arrived, and their trip to memory is saved
+    if (kHand) {
+      load_tile(raw1, v_begin + kTile);
+      if (kDepth == 4) {
+        load_tile(raw2, v_begin + 2 * kTile);
+        load_tile(raw3, v_begin + 3 * kTile);
+      }
+    }
     take_statistics();
 
     // One tile, first half: `raw` holds this lane's entries of the tile that starts at tile0 and is
@@ -652,10 +662,12 @@ __device__ __forceinline__ bool sample_body(const Problem& p, int& n_out, unsign
       lmax0 = tile_noise(raw0, v_begin, true);
       settle();
       __builtin_amdgcn_sched_barrier(0);
-      load_tile(raw1, v_begin + kTile);
-      if (kDepth == 4) {
-        load_tile(raw2, v_begin + 2 * kTile);
-        load_tile(raw3, v_begin + 3 * kTile);
+      if (!kHand) {
+        load_tile(raw1, v_begin + kTile);
+        if (kDepth == 4) {
+          load_tile(raw2, v_begin + 2 * kTile);
+          load_tile(raw3, v_begin + 3 * kTile);
+        }
       }
       load_tile(raw0, v_begin + kDepth * kTile);
       __builtin_amdgcn_sched_barrier(0);
