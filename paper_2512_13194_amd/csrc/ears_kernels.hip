@@ -10,6 +10,8 @@
 //                                         workgroup per chunk, the last to finish a row chooses);
 //                                         when DECIDE and SAMPLE run in one call the scan runs in
 //                                         the filter's prologue
+//   all three    : verify_kernel      - rectangular batches of long rows: the statistics code and
+//                                       the sampling code as the workgroups of ONE launch (verify.h)
 //
 // The path is bound by HBM bandwidth (every needed row is read once, plus one re-read of the row
 // pair the sampler needs): no matrix-core work in it.

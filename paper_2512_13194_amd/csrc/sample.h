@@ -24,9 +24,10 @@
 //
 // Rows the bounds cannot separate (nearly identical target and draft rows, an empty residual,
 // a survivor list that overflows) fall back to an fp64 scan, so the result is always the
-// definition's.  The accept / first-reject scan runs in the filter kernel's prologue (one wave) and
-// the exact choice in its epilogue, so a whole verification is two back-to-back launches: row
-// statistics, then filter and choice (one launch for all of it on small batches: one_launch.h).
+// definition's.  The accept / first-reject scan runs in the filter's prologue (one wave) and the
+// exact choice in its epilogue, so a whole verification is two back-to-back launches: row
+// statistics, then filter and choice; or one launch in which the workgroups that run this code
+// follow those of the statistics (verify.h).
 #pragma once
 
 #include <type_traits>
